@@ -1,0 +1,183 @@
+"""CPU oracle for the selective-recompute partial prefill (TEST INFRASTRUCTURE ONLY).
+
+A plain, slow, float64 NumPy statement of what one layer of CacheTune's online sparse-reuse
+pipeline computes (paper Sec. 4.2, "KV Cache Offloading and Sparse Reuse"), used by the
+tests, the smoke check and the bench's CPU-baseline leg to judge the HIP kernels.  It is
+not part of the product path, shares no code with it and must never be called from it.
+
+The online path is exact given its inputs (the approximation of the method lies in *which*
+tokens are recomputed and in reusing stale KV, both of which are inputs here), so every
+function below is the definition written out, in float64, on bf16-valued inputs, with no
+intermediate rounding:
+
+  qkv_selected        Eq. 1 (k = h W_K, v = h W_V, and likewise q) for the selected tokens,
+                      then standard RoPE at their true positions (Sec. 4.2, "Preserving
+                      positional consistency", last paragraph).
+  rerope_keys         Eq. 8 (deferred RoPE recovery) in its delta form: a key cached after
+                      rotation at `old_pos` is rotated by (new_pos - old_pos).  The paper's
+                      raw pre-RoPE cache is the special case old_pos = 0.
+  scatter_kv          scatter fusion (Sec. 4.2, "Reducing online recomputation and fusion
+                      overhead"): recomputed rows overwrite their slots of the layer buffer.
+  selected_attention  the check/fusion-layer attention "only for the corresponding tokens":
+                      causal softmax attention of the selected queries over the fused KV.
+  partial_prefill_layer  the composition of the four.
+
+Readings where the paper is silent (RoPE pair convention and frequencies, softmax scale,
+GQA head mapping, floor for r*N, V being position independent) are stated at the function
+that uses them.  All pins live in tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+HALF_SPLIT = 0   # pair j couples elements (j, j + D/2)
+INTERLEAVED = 1  # pair j couples elements (2j, 2j + 1)
+
+
+# ----------------------------------------------------------------------------- RoPE
+def rope_frequencies(head_dim: int, theta: float) -> np.ndarray:
+    """omega_j = theta^(-2j/D), j = 0..D/2-1 (the paper only says "RoPE"; this is the
+    standard definition with no long-context scaling)."""
+    j = np.arange(head_dim // 2, dtype=np.float64)
+    return np.float64(theta) ** (-2.0 * j / np.float64(head_dim))
+
+
+def rotate(x: np.ndarray, steps: np.ndarray, theta: float, style: int = HALF_SPLIT) -> np.ndarray:
+    """Rotate every pair of x[t, h, :] by the angle steps[t] * omega_j.
+
+    x: [T, H, D] float64; steps: [T] integers (a position, or a position difference).
+    (x_a, x_b) -> (x_a cos - x_b sin, x_a sin + x_b cos).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    T, H, D = x.shape
+    half = D // 2
+    ang = np.asarray(steps, dtype=np.float64)[:, None] * rope_frequencies(D, theta)[None, :]  # [T, D/2]
+    c = np.cos(ang)[:, None, :]
+    s = np.sin(ang)[:, None, :]
+    out = np.empty_like(x)
+    if style == HALF_SPLIT:
+        a, b = x[..., :half], x[..., half:]
+        out[..., :half] = a * c - b * s
+        out[..., half:] = a * s + b * c
+    elif style == INTERLEAVED:
+        a, b = x[..., 0::2], x[..., 1::2]
+        out[..., 0::2] = a * c - b * s
+        out[..., 1::2] = a * s + b * c
+    else:
+        raise ValueError("rope style")
+    return out
+
+
+# ----------------------------------------------------------------------------- step a1
+def qkv_selected(hidden_sel, wqkv, bias, sel_pos, n_q_heads, n_kv_heads, head_dim, theta,
+                 style: int = HALF_SPLIT):
+    """Fresh Q, K, V for the selected tokens (Eq. 1) with RoPE on Q and K at `sel_pos`.
+
+    hidden_sel: [n, E]; wqkv: [O, E] with O = (Hq + 2 Hkv) D, rows ordered Q heads, K heads,
+    V heads (out-features major, so y = x W^T); bias: [O] or None; sel_pos: [n].
+    Returns q [n, Hq, D], k [n, Hkv, D], v [n, Hkv, D].
+    """
+    x = np.asarray(hidden_sel, dtype=np.float64)
+    w = np.asarray(wqkv, dtype=np.float64)
+    y = x @ w.T
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    n = x.shape[0]
+    nq = n_q_heads * head_dim
+    nk = n_kv_heads * head_dim
+    q = y[:, :nq].reshape(n, n_q_heads, head_dim)
+    k = y[:, nq:nq + nk].reshape(n, n_kv_heads, head_dim)
+    v = y[:, nq + nk:nq + 2 * nk].reshape(n, n_kv_heads, head_dim).copy()
+    q = rotate(q, sel_pos, theta, style)
+    k = rotate(k, sel_pos, theta, style)
+    return q, k, v
+
+
+# ----------------------------------------------------------------------------- step a3
+def rerope_keys(k_cached, old_pos, new_pos, theta, style: int = HALF_SPLIT):
+    """Deferred RoPE recovery (Eq. 8), delta form: rotate row i by new_pos[i] - old_pos[i]."""
+    delta = np.asarray(new_pos, dtype=np.int64) - np.asarray(old_pos, dtype=np.int64)
+    return rotate(k_cached, delta, theta, style)
+
+
+# ----------------------------------------------------------------------------- step a4
+def scatter_kv(k_buf, v_buf, k_sel, v_sel, sel_idx):
+    """Scatter fusion: rows sel_idx of the buffers take the recomputed rows; returns copies."""
+    k_out = np.array(k_buf, copy=True)
+    v_out = np.array(v_buf, copy=True)
+    idx = np.asarray(sel_idx, dtype=np.int64)
+    k_out[idx] = k_sel
+    v_out[idx] = v_sel
+    return k_out, v_out
+
+
+# ----------------------------------------------------------------------------- step a5
+def selected_attention(q_sel, k_buf, v_buf, sel_idx, rows=None, scale=None):
+    """Causal attention of the selected queries over the fused layer KV.
+
+    q_sel: [n, Hq, D]; k_buf, v_buf: [N, Hkv, D]; sel_idx: [n] buffer rows of the queries.
+    Query s sees keys at buffer rows 0..sel_idx[s] inclusive (its own fresh K/V included).
+    Query head h reads KV head h // (Hq/Hkv).  scale defaults to 1/sqrt(D).
+    `rows`: optional ordinals into the selected set; only those outputs are evaluated
+    (each output row depends on no other query, so a subset is exact).
+    Returns out [len(rows), Hq, D] and lse [len(rows), Hq] (natural-log sum of exp of the
+    scaled scores).
+    """
+    q = np.asarray(q_sel, dtype=np.float64)
+    k = np.asarray(k_buf, dtype=np.float64)
+    v = np.asarray(v_buf, dtype=np.float64)
+    idx = np.asarray(sel_idx, dtype=np.int64)
+    if rows is not None:
+        rows = np.asarray(rows, dtype=np.int64)
+        q = q[rows]
+        idx = idx[rows]
+    n, Hq, D = q.shape
+    N, Hkv, _ = k.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    out = np.zeros((n, Hq, D), dtype=np.float64)
+    lse = np.zeros((n, Hq), dtype=np.float64)
+    if n == 0:
+        return out, lse
+    visible = np.arange(N, dtype=np.int64)[None, :] <= idx[:, None]   # [n, N]
+    for h in range(Hq):
+        g = h // G
+        s = (q[:, h, :] @ k[:, g, :].T) * scale                        # [n, N]
+        s = np.where(visible, s, -np.inf)
+        m = s.max(axis=1, keepdims=True)
+        p = np.exp(s - m)
+        l = p.sum(axis=1, keepdims=True)
+        # masked columns carry weight exp(-inf) = 0; zero the operand too so that a
+        # non-finite value parked in an invisible row cannot leak through 0 * inf
+        vh = v[:, g, :]
+        out[:, h, :] = _masked_matmul(p, vh, visible) / l
+        lse[:, h] = (m + np.log(l))[:, 0]
+    return out, lse
+
+
+def _masked_matmul(p, vh, visible):
+    """sum_j p[i, j] * vh[j, :] over the visible j only."""
+    if np.isfinite(vh).all():
+        return p @ vh
+    out = np.empty((p.shape[0], vh.shape[1]), dtype=np.float64)
+    for i in range(p.shape[0]):
+        cols = np.flatnonzero(visible[i])
+        out[i] = p[i, cols] @ vh[cols]
+    return out
+
+
+# ----------------------------------------------------------------------------- step a6
+def partial_prefill_layer(hidden_sel, wqkv, bias, k_cache, v_cache, old_pos, new_pos, sel_idx,
+                          n_q_heads, n_kv_heads, head_dim, theta, style: int = HALF_SPLIT,
+                          rows=None):
+    """One fusion-layer step: recompute the selected tokens, re-rotate the reused keys,
+    scatter, attend.  Returns (attention output for the selected rows, fused K, fused V)."""
+    sel_idx = np.asarray(sel_idx, dtype=np.int64)
+    sel_pos = np.asarray(new_pos, dtype=np.int64)[sel_idx]
+    q, k_new, v_new = qkv_selected(hidden_sel, wqkv, bias, sel_pos, n_q_heads, n_kv_heads,
+                                   head_dim, theta, style)
+    k_rot = rerope_keys(k_cache, old_pos, new_pos, theta, style)
+    k_fused, v_fused = scatter_kv(k_rot, np.asarray(v_cache, dtype=np.float64), k_new, v_new, sel_idx)
+    out, lse = selected_attention(q, k_fused, v_fused, sel_idx, rows=rows)
+    return out, lse, k_fused, v_fused

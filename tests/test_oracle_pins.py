@@ -1,0 +1,335 @@
+"""Pins for the CPU oracle: closed forms, library routines the oracle does not call,
+brute force on tiny inputs and structural identities the paper's text fixes.  Nothing
+here touches the HIP path."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import ct_oracle as O
+
+RNG = np.random.default_rng(20260524)
+
+
+def _rand(*shape):
+    return RNG.standard_normal(shape)
+
+
+# ------------------------------------------------------------------ golden closed forms
+def _golden_lines(path):
+    with open(path) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                yield [float(t) for t in line.split()]
+
+
+def test_rope_closed_form_values(golden_dir):
+    for row in _golden_lines(os.path.join(golden_dir, "rope_unit_rotations.txt")):
+        style, pos = int(row[0]), int(row[1])
+        x = np.array(row[2:6]).reshape(1, 1, 4)
+        want = np.array(row[6:10])
+        got = O.rotate(x, np.array([pos]), 10000.0, style)[0, 0]
+        np.testing.assert_allclose(got, want, atol=1e-13)
+
+
+def test_attention_closed_form_two_keys(golden_dir):
+    D = 4
+    k = np.zeros((2, 1, D)); k[1, 0, 0] = math.sqrt(D) * math.log(3.0)
+    v = np.array([[1, 2, 3, 4], [5, 6, 7, 8]], dtype=np.float64).reshape(2, 1, D)
+    q = np.zeros((2, 1, D)); q[:, 0, 0] = 1.0
+    out, lse = O.selected_attention(q, k, v, np.array([0, 1]))
+    for row in _golden_lines(os.path.join(golden_dir, "softmax_two_keys.txt")):
+        i = int(row[0])
+        np.testing.assert_allclose(out[i, 0], row[1:5], atol=1e-13)
+        np.testing.assert_allclose(lse[i, 0], row[5], atol=1e-13)
+
+
+def test_rope_frequencies_closed_form():
+    w = O.rope_frequencies(128, 500000.0)
+    assert w[0] == 1.0
+    # omega_{D/4} = theta^(-1/2)
+    np.testing.assert_allclose(w[32], 1.0 / math.sqrt(500000.0), rtol=1e-14)
+    np.testing.assert_allclose(w[1:] / w[:-1], 500000.0 ** (-1.0 / 64), rtol=1e-12)
+
+
+# ------------------------------------------------------------------ P2 / P3 rotation group
+@pytest.mark.parametrize("style", [O.HALF_SPLIT, O.INTERLEAVED])
+def test_rotation_group_and_deferred_rope(style):
+    T, H, D, theta = 37, 3, 16, 1.0e4
+    k = _rand(T, H, D)
+    a = RNG.integers(-500, 500, T)
+    b = RNG.integers(-500, 500, T)
+    ab = O.rotate(O.rotate(k, a, theta, style), b, theta, style)
+    np.testing.assert_allclose(ab, O.rotate(k, a + b, theta, style), atol=1e-12)
+    assert np.array_equal(O.rotate(k, np.zeros(T, dtype=int), theta, style), k)
+    np.testing.assert_allclose(O.rotate(O.rotate(k, a, theta, style), -a, theta, style), k, atol=1e-12)
+    # per-pair norm is preserved
+    r = O.rotate(k, a, theta, style)
+    if style == O.HALF_SPLIT:
+        n0 = k[..., :D // 2] ** 2 + k[..., D // 2:] ** 2
+        n1 = r[..., :D // 2] ** 2 + r[..., D // 2:] ** 2
+    else:
+        n0 = k[..., 0::2] ** 2 + k[..., 1::2] ** 2
+        n1 = r[..., 0::2] ** 2 + r[..., 1::2] ** 2
+    np.testing.assert_allclose(n1, n0, rtol=1e-12)
+    # Eq. 8 in delta form: re-rotating a key cached at `old` equals fresh RoPE at `new`
+    old = RNG.integers(0, 300, T)
+    new = RNG.integers(0, 5000, T)
+    cached = O.rotate(k, old, theta, style)
+    np.testing.assert_allclose(O.rerope_keys(cached, old, new, theta, style),
+                               O.rotate(k, new, theta, style), atol=1e-11)
+    # the paper's raw pre-RoPE cache is old_pos = 0
+    np.testing.assert_allclose(O.rerope_keys(k, np.zeros(T, dtype=int), new, theta, style),
+                               O.rotate(k, new, theta, style), atol=0)
+
+
+def test_rotate_matches_complex_multiplication():
+    """RoPE as multiplication by e^{i p omega_j}: an independent formulation (torch.polar)."""
+    T, H, D, theta = 11, 2, 8, 5.0e5
+    x = _rand(T, H, D)
+    pos = RNG.integers(0, 100000, T)
+    w = torch.tensor(theta, dtype=torch.float64) ** (-torch.arange(0, D, 2, dtype=torch.float64) / D)
+    ang = torch.tensor(pos, dtype=torch.float64)[:, None] * w[None, :]
+    e = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+    xt = torch.tensor(x)
+    z = torch.view_as_complex(xt.reshape(T, H, D // 2, 2).contiguous()) * e       # interleaved pairs
+    want_inter = torch.view_as_real(z).reshape(T, H, D).numpy()
+    np.testing.assert_allclose(O.rotate(x, pos, theta, O.INTERLEAVED), want_inter, atol=1e-10)
+    zh = torch.complex(xt[..., :D // 2], xt[..., D // 2:]) * e                    # half-split pairs
+    want_half = torch.cat([zh.real, zh.imag], dim=-1).numpy()
+    np.testing.assert_allclose(O.rotate(x, pos, theta, O.HALF_SPLIT), want_half, atol=1e-10)
+
+
+# ------------------------------------------------------------------ P1 full prefill via library SDPA
+def _torch_full_causal_layer(hidden, wqkv, bias, pos, Hq, Hkv, D, theta, style):
+    """Ordinary full causal prefill of one attention layer with library routines only."""
+    x = torch.tensor(hidden)
+    y = F.linear(x, torch.tensor(wqkv), None if bias is None else torch.tensor(bias))
+    N = x.shape[0]
+    q, k, v = torch.split(y, [Hq * D, Hkv * D, Hkv * D], dim=1)
+    q = q.reshape(N, Hq, D); k = k.reshape(N, Hkv, D); v = v.reshape(N, Hkv, D)
+    w = torch.tensor(theta, dtype=torch.float64) ** (-torch.arange(0, D, 2, dtype=torch.float64) / D)
+    ang = torch.tensor(pos, dtype=torch.float64)[:, None] * w[None, :]
+    e = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+
+    def rope(t):
+        if style == O.INTERLEAVED:
+            z = torch.view_as_complex(t.reshape(N, -1, D // 2, 2).contiguous()) * e
+            return torch.view_as_real(z).reshape(N, -1, D)
+        z = torch.complex(t[..., :D // 2], t[..., D // 2:]) * e
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    q, k = rope(q), rope(k)
+    o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                       v.transpose(0, 1)[None], is_causal=True, enable_gqa=True)
+    return o[0].transpose(0, 1).numpy(), k.numpy(), v.numpy()
+
+
+@pytest.mark.parametrize("style", [O.HALF_SPLIT, O.INTERLEAVED])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2), (6, 1)])
+def test_ratio_100_equals_full_causal_prefill(style, Hq, Hkv):
+    """At r = 100 % the partial path is Full Recompute (Sec. 5 baselines; Fig. 4 caption)."""
+    N, E, D, theta = 48, 24, 8, 1.0e4
+    hidden = _rand(N, E)
+    wqkv = _rand((Hq + 2 * Hkv) * D, E) / math.sqrt(E)
+    bias = _rand((Hq + 2 * Hkv) * D) * 0.1
+    pos = np.arange(N) + 5
+    stale_k = np.full((N, Hkv, D), np.nan)      # every cached row is overwritten
+    stale_v = np.full((N, Hkv, D), np.nan)
+    out, _, kf, vf = O.partial_prefill_layer(hidden, wqkv, bias, stale_k, stale_v,
+                                             np.zeros(N, dtype=int), pos, np.arange(N),
+                                             Hq, Hkv, D, theta, style)
+    want, k_want, v_want = _torch_full_causal_layer(hidden, wqkv, bias, pos, Hq, Hkv, D, theta, style)
+    np.testing.assert_allclose(out, want, atol=1e-10)
+    np.testing.assert_allclose(kf, k_want, atol=1e-10)
+    np.testing.assert_allclose(vf, v_want, atol=1e-10)
+
+
+def test_partial_layer_equals_masked_library_attention():
+    """r < 100 %: selected rows attend over (re-rotated reused K, fresh K) - checked against
+    torch SDPA with an explicit row mask on KV assembled by hand from library pieces."""
+    N, E, Hq, Hkv, D, theta, L = 40, 16, 4, 2, 8, 1.0e4, 10
+    hidden = _rand(N, E)
+    wqkv = _rand((Hq + 2 * Hkv) * D, E) / math.sqrt(E)
+    raw_k = _rand(N, Hkv, D)
+    v_cache = _rand(N, Hkv, D)
+    old = np.arange(N) % L
+    new = np.arange(N)
+    sel = np.sort(RNG.choice(N, 9, replace=False))
+    # cache = raw keys rotated at chunk-local positions (complex formulation, torch)
+    _, k_all_fresh, v_all_fresh = _torch_full_causal_layer(hidden, wqkv, None, new, Hq, Hkv, D, theta, 0)
+    w = torch.tensor(theta, dtype=torch.float64) ** (-torch.arange(0, D, 2, dtype=torch.float64) / D)
+
+    def rope_t(t, p):
+        ang = torch.tensor(p, dtype=torch.float64)[:, None] * w[None, :]
+        e = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+        z = torch.complex(t[..., :D // 2], t[..., D // 2:]) * e
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    k_cache = rope_t(torch.tensor(raw_k), old).numpy()
+    k_fused = rope_t(torch.tensor(raw_k), new).numpy()       # what Eq. 8 must reproduce
+    v_fused = v_cache.copy()
+    k_fused[sel] = k_all_fresh[sel]
+    v_fused[sel] = v_all_fresh[sel]
+    y = F.linear(torch.tensor(hidden[sel]), torch.tensor(wqkv))
+    q = rope_t(y[:, :Hq * D].reshape(-1, Hq, D), new[sel])
+    mask = torch.tensor(np.arange(N)[None, :] <= sel[:, None])
+    want = F.scaled_dot_product_attention(q.transpose(0, 1)[None],
+                                          torch.tensor(k_fused).transpose(0, 1)[None],
+                                          torch.tensor(v_fused).transpose(0, 1)[None],
+                                          attn_mask=mask, enable_gqa=True)[0].transpose(0, 1).numpy()
+    out, _, kf, vf = O.partial_prefill_layer(hidden[sel], wqkv, None, k_cache, v_cache, old, new, sel,
+                                             Hq, Hkv, D, theta)
+    np.testing.assert_allclose(kf, k_fused, atol=1e-10)
+    np.testing.assert_allclose(vf, v_fused, atol=0)
+    np.testing.assert_allclose(out, want, atol=1e-10)
+
+
+# ------------------------------------------------------------------ P4 brute force
+def _brute_layer(hidden_sel, wqkv, k_cache, v_cache, old, new, sel, Hq, Hkv, D, theta, style):
+    """Scalar loops with math.cos / math.sin / math.exp only."""
+    n, E = len(sel), len(hidden_sel[0])
+    N = len(k_cache)
+    G = Hq // Hkv
+
+    def pair(j):
+        return (j, j + D // 2) if style == 0 else (2 * j, 2 * j + 1)
+
+    def rot(vec, steps):
+        o = list(vec)
+        for j in range(D // 2):
+            a, b = pair(j)
+            ang = steps * theta ** (-2.0 * j / D)
+            o[a] = vec[a] * math.cos(ang) - vec[b] * math.sin(ang)
+            o[b] = vec[a] * math.sin(ang) + vec[b] * math.cos(ang)
+        return o
+
+    K = [[rot(list(k_cache[i][g]), int(new[i]) - int(old[i])) for g in range(Hkv)] for i in range(N)]
+    V = [[list(v_cache[i][g]) for g in range(Hkv)] for i in range(N)]
+    Q = []
+    for s in range(n):
+        y = [sum(hidden_sel[s][e] * wqkv[o][e] for e in range(E)) for o in range((Hq + 2 * Hkv) * D)]
+        p = int(new[sel[s]])
+        Q.append([rot(y[h * D:(h + 1) * D], p) for h in range(Hq)])
+        for g in range(Hkv):
+            K[sel[s]][g] = rot(y[(Hq + g) * D:(Hq + g + 1) * D], p)
+            V[sel[s]][g] = y[(Hq + Hkv + g) * D:(Hq + Hkv + g + 1) * D]
+    out = np.zeros((n, Hq, D))
+    for s in range(n):
+        for h in range(Hq):
+            g = h // G
+            sc = [sum(Q[s][h][d] * K[j][g][d] for d in range(D)) / math.sqrt(D) for j in range(sel[s] + 1)]
+            mx = max(sc)
+            wgt = [math.exp(x - mx) for x in sc]
+            tot = sum(wgt)
+            for d in range(D):
+                out[s, h, d] = sum(wgt[j] * V[j][g][d] for j in range(sel[s] + 1)) / tot
+    return out
+
+
+@pytest.mark.parametrize("style", [0, 1])
+@pytest.mark.parametrize("Hq,Hkv,D", [(1, 1, 4), (4, 2, 8)])
+@pytest.mark.parametrize("n_sel", [1, 7, 24])
+def test_brute_force_tiny(style, Hq, Hkv, D, n_sel):
+    N, E, theta, L = 24, 6, 100.0, 8
+    hidden = _rand(N, E)
+    wqkv = _rand((Hq + 2 * Hkv) * D, E)
+    k_cache, v_cache = _rand(N, Hkv, D), _rand(N, Hkv, D)
+    old, new = np.arange(N) % L, np.arange(N) + 3
+    sel = np.sort(RNG.choice(N, n_sel, replace=False))
+    want = _brute_layer(hidden[sel].tolist(), wqkv.tolist(), k_cache.tolist(), v_cache.tolist(),
+                        old, new, sel.tolist(), Hq, Hkv, D, theta, style)
+    out, *_ = O.partial_prefill_layer(hidden[sel], wqkv, None, k_cache, v_cache, old, new, sel,
+                                      Hq, Hkv, D, theta, style)
+    np.testing.assert_allclose(out, want, atol=1e-11)
+
+
+# ------------------------------------------------------------------ P5 translation invariance
+def test_translation_invariance_of_positions():
+    N, E, Hq, Hkv, D, theta = 32, 12, 4, 2, 8, 1.0e4
+    hidden, wqkv = _rand(N, E), _rand((Hq + 2 * Hkv) * D, E)
+    raw_k, v_cache = _rand(N, Hkv, D), _rand(N, Hkv, D)
+    old = np.arange(N) % 8
+    k_cache = O.rotate(raw_k, old, theta)
+    sel = np.sort(RNG.choice(N, 10, replace=False))
+    outs = []
+    for shift in (0, 1234):
+        new = np.arange(N) + shift
+        out, *_ = O.partial_prefill_layer(hidden[sel], wqkv, None, k_cache, v_cache, old, new, sel,
+                                          Hq, Hkv, D, theta)
+        outs.append(out)
+    np.testing.assert_allclose(outs[0], outs[1], atol=1e-9)
+
+
+# ------------------------------------------------------------------ P6 textbook reductions
+def test_first_row_and_equal_keys_and_gqa_replication():
+    N, Hq, Hkv, D = 20, 4, 2, 8
+    q, k, v = _rand(N, Hq, D), _rand(N, Hkv, D), _rand(N, Hkv, D)
+    sel = np.arange(N)
+    out, lse = O.selected_attention(q, k, v, sel)
+    # row 0 sees only key 0
+    for h in range(Hq):
+        np.testing.assert_allclose(out[0, h], v[0, h // 2], atol=1e-14)
+        np.testing.assert_allclose(lse[0, h], q[0, h] @ k[0, h // 2] / math.sqrt(D), atol=1e-13)
+    # all keys equal -> running mean of V
+    k_same = np.broadcast_to(k[:1], k.shape)
+    out2, _ = O.selected_attention(q, k_same, v, sel)
+    mean = np.cumsum(v, axis=0) / np.arange(1, N + 1)[:, None, None]
+    for h in range(Hq):
+        np.testing.assert_allclose(out2[:, h], mean[:, h // 2], atol=1e-12)
+    # GQA == MHA with KV heads replicated
+    out3, _ = O.selected_attention(q, np.repeat(k, 2, axis=1), np.repeat(v, 2, axis=1), sel)
+    np.testing.assert_allclose(out3, out, atol=1e-14)
+    # a subset of rows equals the same rows of the full evaluation
+    rows = np.array([0, 3, 19])
+    out4, lse4 = O.selected_attention(q, k, v, sel, rows=rows)
+    np.testing.assert_array_equal(out4, out[rows])
+    np.testing.assert_array_equal(lse4, lse[rows])
+
+
+# ------------------------------------------------------------------ P7 locality
+def test_locality_future_rows_and_stale_slots_do_not_matter():
+    N, E, Hq, Hkv, D, theta = 32, 12, 4, 2, 8, 1.0e4
+    hidden, wqkv = _rand(N, E), _rand((Hq + 2 * Hkv) * D, E)
+    k_cache, v_cache = _rand(N, Hkv, D), _rand(N, Hkv, D)
+    old, new = np.arange(N) % 8, np.arange(N)
+    sel = np.array([2, 5, 9, 17, 20])
+    base, *_ = O.partial_prefill_layer(hidden[sel], wqkv, None, k_cache, v_cache, old, new, sel,
+                                       Hq, Hkv, D, theta)
+    k2, v2 = k_cache.copy(), v_cache.copy()
+    k2[sel] = np.nan; v2[sel] = np.nan          # stale slots are never read
+    k2[21:] = np.nan; v2[21:] = np.nan          # rows after the last query are never read
+    with np.errstate(invalid="ignore"):
+        out, *_ = O.partial_prefill_layer(hidden[sel], wqkv, None, k2, v2, old, new, sel,
+                                          Hq, Hkv, D, theta)
+    assert np.isfinite(out).all()
+    np.testing.assert_allclose(out, base, atol=1e-13)   # same terms, different summation order
+
+
+# ------------------------------------------------------------------ P8 scatter
+def test_scatter_is_bit_exact_and_touches_only_selected_rows():
+    N, Hkv, D = 50, 2, 8
+    kb, vb = _rand(N, Hkv, D), _rand(N, Hkv, D)
+    sel = np.sort(RNG.choice(N, 13, replace=False))
+    ks, vs = _rand(13, Hkv, D), _rand(13, Hkv, D)
+    k2, v2 = O.scatter_kv(kb, vb, ks, vs, sel)
+    assert np.array_equal(k2[sel], ks) and np.array_equal(v2[sel], vs)
+    rest = np.setdiff1d(np.arange(N), sel)
+    assert np.array_equal(k2[rest], kb[rest]) and np.array_equal(v2[rest], vb[rest])
+    assert not np.shares_memory(k2, kb)
+
+
+def test_empty_selection_is_full_reuse():
+    """r = 0 (Full KV Reuse): nothing is recomputed, the fused cache is the re-rotated cache."""
+    N, Hkv, D, theta = 12, 2, 8, 1.0e4
+    k_cache, v_cache = _rand(N, Hkv, D), _rand(N, Hkv, D)
+    old, new = np.arange(N) % 4, np.arange(N)
+    out, lse, kf, vf = O.partial_prefill_layer(np.zeros((0, 6)), _rand(4 * 2 * D, 6), None, k_cache, v_cache,
+                                               old, new, np.zeros(0, dtype=int), 4, Hkv, D, theta)
+    assert out.shape == (0, 4, D)
+    np.testing.assert_allclose(kf, O.rotate(k_cache, new - old, theta), atol=0)
+    assert np.array_equal(vf, v_cache)
