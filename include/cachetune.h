@@ -1,0 +1,190 @@
+/*
+ * cachetune.h - C ABI of the MI355X (gfx950) selective-recompute partial-prefill library.
+ *
+ * The library implements one layer of CacheTune's online sparse-reuse pipeline (paper
+ * Sec. 4.2, "KV Cache Offloading and Sparse Reuse"): cached KV chunks are reused at new
+ * positions, only the tokens of a recompute index set are projected again, the two parts
+ * are fused in one layer buffer and the selected tokens' queries attend causally over it.
+ *
+ * Conventions shared by every entry point
+ *   - All tensors are dense, row-major bfloat16 unless stated otherwise; index and position
+ *     vectors are int32.  "device" pointers are HIP device memory of the current device,
+ *     "host" pointers are ordinary process memory, "pinned host" is hipHostMalloc memory.
+ *   - KV layout is token-major [tokens, n_kv_heads, head_dim] (the paper's N x H x D).
+ *   - The caller owns every buffer and both streams.  The library allocates nothing and
+ *     keeps no state besides a thread-local error string.  `stream` arguments are
+ *     hipStream_t values passed as void* (NULL = the default stream).
+ *   - Calls only enqueue work: no entry point synchronises the device or the host with it.
+ *     Results are valid once the stream has passed the call's last kernel.
+ *   - Every host-checkable condition (NULL pointers, shapes, chunk tiling, workspace size,
+ *     the ratio) is checked before the first HIP call and reported as a negative status;
+ *     nothing is thrown and nothing aborts.  ct_last_error() describes the last failure of
+ *     the calling thread.
+ *   - Supported shapes: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads with
+ *     group size n_q_heads / n_kv_heads in {1, 2, 4, 8, 16}; hidden a multiple of 64.
+ */
+#ifndef CACHETUNE_H
+#define CACHETUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CT_OK = 0,
+  CT_ERR_NULL = -1,        /* a required pointer is NULL */
+  CT_ERR_SHAPE = -2,       /* a size is negative, zero where it may not be, or inconsistent */
+  CT_ERR_INDEX = -3,       /* host index set not strictly ascending / out of range */
+  CT_ERR_RATIO = -4,       /* n_sel does not equal floor(recompute_ratio * n_ctx) */
+  CT_ERR_WORKSPACE = -5,   /* workspace missing or smaller than ct_workspace_bytes() */
+  CT_ERR_HIP = -6,         /* a HIP runtime call failed; see ct_last_error() */
+  CT_ERR_UNSUPPORTED = -7  /* a shape outside the supported set listed above */
+} ct_status;
+
+/* One attention layer's shape.  RoPE: omega_j = rope_theta^(-2j/head_dim); rope_style 0
+ * couples elements (j, j + head_dim/2), rope_style 1 couples (2j, 2j + 1).
+ * softmax_scale 0 means 1/sqrt(head_dim). */
+typedef struct {
+  int32_t hidden;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  double rope_theta;
+  int32_t rope_style;
+  float softmax_scale;
+} ct_layer_cfg;
+
+/* One reusable KV chunk (the paper's unit of storage and transfer, Sec. 3 and 4.2).
+ * k, v: bf16 [n_tokens, n_kv_heads, head_dim], device memory (location 0) or pinned host
+ * memory (location 1).  In the new context token t of the chunk sits at position
+ * new_pos_start + t.  raw_keys = 0: the keys were cached after RoPE at positions
+ * old_pos_start + t and are rotated by new_pos_start - old_pos_start.  raw_keys = 1: the
+ * keys were cached before RoPE (the paper's own scheme, Eq. 8) and token t is rotated by
+ * new_pos_start + t; old_pos_start is ignored. */
+typedef struct {
+  const void* k;
+  const void* v;
+  int32_t n_tokens;
+  int32_t old_pos_start;
+  int32_t new_pos_start;
+  int32_t location;
+  int32_t raw_keys;
+  int32_t reserved;
+} ct_chunk;
+
+/* Step "selective recompute" (Eq. 1 and Sec. 4.2 last paragraph: standard RoPE at the true
+ * positions).  For s in [0, n_sel): x = hidden[hidden_rows ? hidden_rows[s] : s, :],
+ * [q|k|v] = x * wqkv^T (+ bias), RoPE on every q and k head at position sel_pos[s],
+ * results rounded to bf16 (nearest even) from fp32 accumulators.
+ *   hidden      device bf16 [*, hidden]
+ *   hidden_rows device int32 [n_sel] or NULL (hidden is already compact)
+ *   sel_pos     device int32 [n_sel]
+ *   wqkv        device bf16 [(n_q_heads + 2 n_kv_heads) * head_dim, hidden]: one row per
+ *               output feature (q heads, then k heads, then v heads)
+ *   bias        device bf16 [(n_q_heads + 2 n_kv_heads) * head_dim] or NULL
+ *   q_out       device bf16 [n_sel, n_q_heads, head_dim]
+ *   k_out,v_out device bf16 [n_sel, n_kv_heads, head_dim]
+ * n_sel = 0 is legal and does nothing. */
+ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows,
+                          const int32_t* sel_pos, int32_t n_sel, const void* wqkv, const void* bias,
+                          void* q_out, void* k_out, void* v_out, void* stream);
+
+/* Step "deferred RoPE recovery" (Eq. 8) in delta form: key row t is rotated by the angle
+ * (new_pos[t] - old_pos[t]) * omega_j in fp32 (angle reduced in fp64) and rounded to bf16.
+ *   k_src, k_dst device bf16 [n_tokens, n_kv_heads, head_dim]; k_dst may equal k_src
+ *                (in place) but may not otherwise overlap it
+ *   old_pos      device int32 [n_tokens] or NULL (= all zero: a raw pre-RoPE cache)
+ *   new_pos      device int32 [n_tokens] */
+ct_status ct_rerope_keys(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const int32_t* old_pos,
+                         const int32_t* new_pos, int32_t n_tokens, void* stream);
+
+/* Same rotation for one chunk whose positions are contiguous (Eq. 8): token t moves from
+ * old_pos_start + t to new_pos_start + t, so every token shares one delta; with
+ * raw_keys != 0 token t is rotated by new_pos_start + t instead.  If v_src and v_dst are
+ * both non-NULL and differ, the chunk's values are copied alongside (values carry no
+ * position: Sec. 4.2 corrects Keys only). */
+ct_status ct_rerope_chunk(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src,
+                          void* v_dst, int32_t n_tokens, int32_t old_pos_start, int32_t new_pos_start,
+                          int32_t raw_keys, void* stream);
+
+/* Step "scatter fusion" (Sec. 4.2): k_buf[sel_idx[s]] = k_sel[s], v_buf[sel_idx[s]] = v_sel[s],
+ * bit for bit; no other row is touched.
+ *   k_buf, v_buf device bf16 [n_ctx, n_kv_heads, head_dim] (in/out)
+ *   k_sel, v_sel device bf16 [n_sel, n_kv_heads, head_dim]
+ *   sel_idx      device int32 [n_sel], strictly ascending, in [0, n_ctx) (not checked on
+ *                the device; use ct_validate_indices on a host copy) */
+ct_status ct_scatter_kv(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, int32_t n_ctx, const void* k_sel,
+                        const void* v_sel, const int32_t* sel_idx, int32_t n_sel, void* stream);
+
+/* Step "attention only for the selected tokens" (Sec. 4.2, check/fusion layers): for every
+ * selected token s and query head h,
+ *   out[s,h,:] = sum_{j <= sel_idx[s]} softmax_j(q[s,h,:] . k_buf[j,g,:] * scale) v_buf[j,g,:],
+ * g = h / (n_q_heads / n_kv_heads).  bf16 operands, fp32 scores / softmax / accumulation.
+ *   q_sel  device bf16 [n_sel, n_q_heads, head_dim]
+ *   out    device bf16 [n_sel, n_q_heads, head_dim]
+ *   lse    device fp32 [n_sel, n_q_heads] natural-log sum-exp of the scaled scores, or NULL
+ *   workspace device scratch of at least ct_workspace_bytes(cfg, n_ctx, n_sel) bytes,
+ *          256-byte aligned; contents are undefined afterwards. */
+ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
+                                int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* One fusion-layer step of the online pipeline (Sec. 4.2; its cost model is Eq. 9):
+ *   compute stream: selective recompute of q/k/v for the selected rows
+ *   copy stream   : for chunks in pinned host memory, K and V rows -> k_buf / v_buf, one
+ *                   event per chunk (the "Transfer stream")
+ *   compute stream: per chunk, wait for its copy, re-rotate its keys into place (device
+ *                   chunks are read from chunk.k / chunk.v and written to the buffers;
+ *                   a device chunk whose k already points at its rows of k_buf is rotated
+ *                   in place and its v is left alone)
+ *   compute stream: scatter, then selected-row attention.
+ * Chunks must tile buffer rows [0, n_ctx) in order (n_ctx = sum of n_tokens) with ascending
+ * new positions, so that "key position <= query position" is "key row <= query row".
+ *   hidden / hidden_rows / wqkv / bias as in ct_qkv_selected; the RoPE position of selected
+ *   token s is the new position of buffer row sel_idx[s].
+ *   sel_idx      device int32 [n_sel] strictly ascending
+ *   recompute_ratio  r in [0,1]: n_sel must equal floor(r * n_ctx) (1 at least when r > 0);
+ *                a negative value disables the check
+ *   attn_out     device bf16 [n_sel, n_q_heads, head_dim]
+ *   workspace    at least ct_workspace_bytes(cfg, n_ctx, n_sel) bytes
+ *   copy_stream  used only when a chunk has location 1; must differ from compute_stream
+ *                for the copy to overlap.
+ * On return (stream ordered) k_buf / v_buf hold the fused layer KV.  n_sel = 0 is the Full
+ * KV Reuse case: the buffers are assembled and no attention output is produced. */
+ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chunks, int32_t n_chunks,
+                                   const void* hidden, const int32_t* hidden_rows, const int32_t* sel_idx,
+                                   int32_t n_sel, double recompute_ratio, const void* wqkv, const void* bias,
+                                   void* k_buf, void* v_buf, void* attn_out, void* workspace,
+                                   size_t workspace_bytes, void* compute_stream, void* copy_stream);
+
+/* Scratch bytes ct_selected_attention / ct_partial_prefill_layer need for this problem
+ * size (0 on invalid arguments). */
+size_t ct_workspace_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel);
+
+/* Host-side check of an index set: strictly ascending and inside [0, n_ctx). */
+ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_ctx);
+
+/* Per-kernel timing for measurement runs.  With profiling on, every kernel launch the
+ * library makes is bracketed by a pair of HIP events recorded on the launch stream.
+ * ct_profile_read waits for the recorded events of one kernel class, adds their elapsed
+ * times and returns the number of launches and the summed milliseconds; ct_profile_reset
+ * forgets what was recorded.  Classes: 0 qkv projection, 1 re-RoPE, 2 scatter,
+ * 3 selected attention (main kernel), 4 attention split merge.  Profiling is process wide,
+ * off by default, creates events on first use and is not meant for concurrent callers. */
+void ct_set_profiling(int32_t on);
+void ct_profile_reset(void);
+ct_status ct_profile_read(int32_t kernel_class, int64_t* launches, double* total_ms);
+
+/* Message for the last non-OK status returned on this thread ("" if none). */
+const char* ct_last_error(void);
+
+/* Library version string. */
+const char* ct_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CACHETUNE_H */

@@ -1,0 +1,445 @@
+// Host side of libcachetune: argument validation (before any HIP call), error reporting,
+// opt-in event profiling and the stream/event orchestration of one partial-prefill layer
+// (Sec. 4.2: Transfer stream + Recompute stream coordinated by events; cost model Eq. 9).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "ct_internal.h"
+
+namespace ct {
+
+// ------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+ct_status fail(ct_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+ct_status hip_fail(hipError_t e, const char* what) {
+  return fail(CT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+ct_status check_cfg(const ct_layer_cfg* cfg) {
+  if (cfg == nullptr) return fail(CT_ERR_NULL, "cfg is NULL");
+  if (cfg->hidden <= 0 || cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->head_dim <= 0)
+    return fail(CT_ERR_SHAPE, "cfg sizes must be positive (hidden %d, heads %d/%d, head_dim %d)", cfg->hidden,
+                cfg->n_q_heads, cfg->n_kv_heads, cfg->head_dim);
+  if (cfg->n_q_heads % cfg->n_kv_heads != 0)
+    return fail(CT_ERR_SHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", cfg->n_q_heads, cfg->n_kv_heads);
+  if (cfg->head_dim != 64 && cfg->head_dim != 128)
+    return fail(CT_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128 are supported", cfg->head_dim);
+  const int g = cfg->n_q_heads / cfg->n_kv_heads;
+  if (!is_pow2(g) || g > 16) return fail(CT_ERR_UNSUPPORTED, "group size %d: supported are 1, 2, 4, 8, 16", g);
+  if (cfg->hidden % 64 != 0) return fail(CT_ERR_UNSUPPORTED, "hidden %d is not a multiple of 64", cfg->hidden);
+  if (cfg->rope_style != 0 && cfg->rope_style != 1)
+    return fail(CT_ERR_UNSUPPORTED, "rope_style %d: 0 (half-split) or 1 (interleaved)", cfg->rope_style);
+  if (!(cfg->rope_theta > 0.0) || !isfinite(cfg->rope_theta))
+    return fail(CT_ERR_SHAPE, "rope_theta must be positive and finite");
+  if (!(cfg->softmax_scale >= 0.0f) || !isfinite(cfg->softmax_scale))
+    return fail(CT_ERR_SHAPE, "softmax_scale must be >= 0 (0 selects 1/sqrt(head_dim))");
+  return CT_OK;
+}
+
+void fill_rope_table(const ct_layer_cfg* cfg, RopeTable* t) {
+  const int half = cfg->head_dim / 2;
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int j = 0; j < 64; ++j) {
+    t->turns[j] = j < half ? pow(cfg->rope_theta, -2.0 * (double)j / (double)cfg->head_dim) / two_pi : 0.0;
+  }
+}
+
+// ------------------------------------------------------------------------------ profiling
+struct ProfClass {
+  std::vector<hipEvent_t> start, stop;
+  size_t used = 0;
+};
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static ProfClass g_prof[KC_COUNT];
+
+int prof_begin(KernelClass kc, hipStream_t s) {
+  if (!g_prof_on) return -1;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  ProfClass& p = g_prof[kc];
+  if (p.used == p.start.size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return -1;
+    if (hipEventCreate(&b) != hipSuccess) {
+      (void)hipEventDestroy(a);
+      return -1;
+    }
+    p.start.push_back(a);
+    p.stop.push_back(b);
+  }
+  int slot = (int)p.used++;
+  (void)hipEventRecord(p.start[slot], s);
+  return slot;
+}
+
+void prof_end(KernelClass kc, int slot, hipStream_t s) {
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  (void)hipEventRecord(g_prof[kc].stop[slot], s);
+}
+
+// ------------------------------------------------------------------------------ planning
+AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
+  AttnPlan p;
+  const int g = cfg->n_q_heads / cfg->n_kv_heads;
+  p.tile_tokens = 256 / g;
+  p.n_tiles = (n_sel + p.tile_tokens - 1) / p.tile_tokens;
+  p.n_splits = 1;
+  p.split_keys = n_ctx;
+  p.ws_bytes = 0;
+  // Split the key range when (tile, kv head) pairs alone cannot fill 256 compute units a few
+  // times over; each split writes fp32 partial (O, m, l) to the workspace and a merge kernel
+  // combines them.
+  const long pairs = (long)p.n_tiles * cfg->n_kv_heads;
+  if (pairs > 0 && pairs < 2048 && n_ctx > 2048) {
+    int want = (int)((2048 + pairs - 1) / pairs);       // splits needed for ~8 items per CU (half are empty: causal)
+    int keys = (n_ctx + want - 1) / want;
+    keys = ((keys + 1023) / 1024) * 1024;               // whole K tiles, not too small
+    if (keys < 2048) keys = 2048;
+    int ns = (n_ctx + keys - 1) / keys;
+    if (ns > 1) {
+      p.n_splits = ns;
+      p.split_keys = keys;
+      const size_t cols = 256;
+      const size_t per_item = cols * (size_t)(cfg->head_dim + 2) * sizeof(float);
+      p.ws_bytes = (size_t)p.n_tiles * cfg->n_kv_heads * ns * per_item;
+    }
+  }
+  return p;
+}
+
+static ct_status check_indices_host(const int32_t* idx, int32_t n_sel, int32_t n_ctx) {
+  for (int32_t i = 0; i < n_sel; ++i) {
+    if (idx[i] < 0 || idx[i] >= n_ctx)
+      return fail(CT_ERR_INDEX, "index %d at ordinal %d is outside [0, %d)", idx[i], i, n_ctx);
+    if (i > 0 && idx[i] <= idx[i - 1])
+      return fail(CT_ERR_INDEX, "indices not strictly ascending at ordinal %d (%d after %d)", i, idx[i], idx[i - 1]);
+  }
+  return CT_OK;
+}
+
+}  // namespace ct
+
+using namespace ct;
+
+// ================================================================================ C ABI
+extern "C" {
+
+const char* ct_last_error(void) { return g_err; }
+const char* ct_version(void) { return "cachetune-gfx950 0.1"; }
+
+void ct_set_profiling(int32_t on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+}
+
+void ct_profile_reset(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (int i = 0; i < KC_COUNT; ++i) g_prof[i].used = 0;
+}
+
+ct_status ct_profile_read(int32_t kernel_class, int64_t* launches, double* total_ms) {
+  if (launches == nullptr || total_ms == nullptr) return fail(CT_ERR_NULL, "launches / total_ms is NULL");
+  if (kernel_class < 0 || kernel_class >= KC_COUNT) return fail(CT_ERR_SHAPE, "kernel class %d unknown", kernel_class);
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  ProfClass& p = g_prof[kernel_class];
+  double sum = 0.0;
+  for (size_t i = 0; i < p.used; ++i) {
+    hipError_t e = hipEventSynchronize(p.stop[i]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize (profile)");
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, p.start[i], p.stop[i]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime (profile)");
+    sum += ms;
+  }
+  *launches = (int64_t)p.used;
+  *total_ms = sum;
+  return CT_OK;
+}
+
+ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_ctx) {
+  if (n_sel < 0 || n_ctx < 0) return fail(CT_ERR_SHAPE, "negative size (n_sel %d, n_ctx %d)", n_sel, n_ctx);
+  if (n_sel > n_ctx) return fail(CT_ERR_SHAPE, "n_sel %d exceeds n_ctx %d", n_sel, n_ctx);
+  if (n_sel > 0 && host_idx == nullptr) return fail(CT_ERR_NULL, "host_idx is NULL");
+  return check_indices_host(host_idx, n_sel, n_ctx);
+}
+
+size_t ct_workspace_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel) {
+  if (check_cfg(cfg) != CT_OK || n_ctx <= 0 || n_sel < 0 || n_sel > n_ctx) return 0;
+  // selected-row attention partials (if the key range is split) + the layer call's staging of
+  // recomputed q, k, v rows, each region 256-byte aligned
+  AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  const size_t q = up((size_t)n_sel * cfg->n_q_heads * cfg->head_dim * 2);
+  const size_t kv = up((size_t)n_sel * cfg->n_kv_heads * cfg->head_dim * 2);
+  return up(p.ws_bytes) + q + 2 * kv + 256;
+}
+
+ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows,
+                          const int32_t* sel_pos, int32_t n_sel, const void* wqkv, const void* bias, void* q_out,
+                          void* k_out, void* v_out, void* stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (n_sel < 0) return fail(CT_ERR_SHAPE, "n_sel %d is negative", n_sel);
+  if (n_sel == 0) return CT_OK;
+  if (!hidden || !sel_pos || !wqkv || !q_out || !k_out || !v_out)
+    return fail(CT_ERR_NULL, "hidden, sel_pos, wqkv, q_out, k_out and v_out must be non-NULL");
+  return launch_qkv(cfg, hidden, hidden_rows, sel_pos, nullptr, nullptr, n_sel, wqkv, bias, q_out, k_out, v_out,
+                    static_cast<hipStream_t>(stream));
+}
+
+ct_status ct_rerope_keys(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const int32_t* old_pos,
+                         const int32_t* new_pos, int32_t n_tokens, void* stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (n_tokens < 0) return fail(CT_ERR_SHAPE, "n_tokens %d is negative", n_tokens);
+  if (n_tokens == 0) return CT_OK;
+  if (!k_src || !k_dst || !new_pos) return fail(CT_ERR_NULL, "k_src, k_dst and new_pos must be non-NULL");
+  return launch_rerope(cfg, k_src, k_dst, nullptr, nullptr, old_pos, new_pos, 0, 0, n_tokens,
+                       static_cast<hipStream_t>(stream));
+}
+
+ct_status ct_rerope_chunk(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src, void* v_dst,
+                          int32_t n_tokens, int32_t old_pos_start, int32_t new_pos_start, int32_t raw_keys,
+                          void* stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (n_tokens < 0) return fail(CT_ERR_SHAPE, "n_tokens %d is negative", n_tokens);
+  if (n_tokens == 0) return CT_OK;
+  if (!k_src || !k_dst) return fail(CT_ERR_NULL, "k_src and k_dst must be non-NULL");
+  if ((v_src == nullptr) != (v_dst == nullptr)) return fail(CT_ERR_NULL, "v_src and v_dst must be given together");
+  const bool copy_v = v_src != nullptr && v_src != v_dst;
+  const int32_t d0 = raw_keys ? new_pos_start : new_pos_start - old_pos_start;
+  return launch_rerope(cfg, k_src, k_dst, copy_v ? v_src : nullptr, copy_v ? v_dst : nullptr, nullptr, nullptr, d0,
+                       raw_keys ? 1 : 0, n_tokens, static_cast<hipStream_t>(stream));
+}
+
+ct_status ct_scatter_kv(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, int32_t n_ctx, const void* k_sel,
+                        const void* v_sel, const int32_t* sel_idx, int32_t n_sel, void* stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (n_ctx < 0 || n_sel < 0) return fail(CT_ERR_SHAPE, "negative size (n_ctx %d, n_sel %d)", n_ctx, n_sel);
+  if (n_sel > n_ctx) return fail(CT_ERR_SHAPE, "n_sel %d exceeds n_ctx %d", n_sel, n_ctx);
+  if (n_sel == 0) return CT_OK;
+  if (!k_buf || !v_buf || !k_sel || !v_sel || !sel_idx)
+    return fail(CT_ERR_NULL, "k_buf, v_buf, k_sel, v_sel and sel_idx must be non-NULL");
+  return launch_scatter(cfg, k_buf, v_buf, k_sel, v_sel, sel_idx, n_sel, static_cast<hipStream_t>(stream));
+}
+
+ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
+                                int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (n_ctx <= 0 || n_sel < 0) return fail(CT_ERR_SHAPE, "bad size (n_ctx %d, n_sel %d)", n_ctx, n_sel);
+  if (n_sel > n_ctx) return fail(CT_ERR_SHAPE, "n_sel %d exceeds n_ctx %d", n_sel, n_ctx);
+  if (n_sel == 0) return CT_OK;
+  if (!q_sel || !k_buf || !v_buf || !sel_idx || !out)
+    return fail(CT_ERR_NULL, "q_sel, k_buf, v_buf, sel_idx and out must be non-NULL");
+  AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
+  if (p.ws_bytes > 0) {
+    if (workspace == nullptr) return fail(CT_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", p.ws_bytes);
+    if (workspace_bytes < p.ws_bytes)
+      return fail(CT_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.ws_bytes);
+    if (((uintptr_t)workspace & 255) != 0) return fail(CT_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  }
+  return launch_attention(cfg, q_sel, k_buf, v_buf, n_ctx, sel_idx, n_sel, out, lse, workspace,
+                          static_cast<hipStream_t>(stream));
+}
+
+ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chunks, int32_t n_chunks,
+                                   const void* hidden, const int32_t* hidden_rows, const int32_t* sel_idx,
+                                   int32_t n_sel, double recompute_ratio, const void* wqkv, const void* bias,
+                                   void* k_buf, void* v_buf, void* attn_out, void* workspace,
+                                   size_t workspace_bytes, void* compute_stream, void* copy_stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (chunks == nullptr) return fail(CT_ERR_NULL, "chunks is NULL");
+  if (n_chunks <= 0) return fail(CT_ERR_SHAPE, "n_chunks %d must be positive", n_chunks);
+  if (n_chunks > 64) return fail(CT_ERR_UNSUPPORTED, "n_chunks %d: at most 64 chunks per call", n_chunks);
+  if (n_sel < 0) return fail(CT_ERR_SHAPE, "n_sel %d is negative", n_sel);
+
+  ChunkTable tab;
+  memset(&tab, 0, sizeof(tab));
+  tab.n = n_chunks;
+  int64_t n_ctx64 = 0;
+  bool any_host = false;
+  for (int c = 0; c < n_chunks; ++c) {
+    const ct_chunk& ch = chunks[c];
+    if (ch.n_tokens <= 0) return fail(CT_ERR_SHAPE, "chunk %d has n_tokens %d", c, ch.n_tokens);
+    if (ch.k == nullptr || ch.v == nullptr) return fail(CT_ERR_NULL, "chunk %d has a NULL k or v", c);
+    if (ch.location != 0 && ch.location != 1) return fail(CT_ERR_SHAPE, "chunk %d has location %d", c, ch.location);
+    if (ch.new_pos_start < 0) return fail(CT_ERR_SHAPE, "chunk %d has negative new_pos_start", c);
+    if (c > 0) {
+      const ct_chunk& pr = chunks[c - 1];
+      if ((int64_t)ch.new_pos_start < (int64_t)pr.new_pos_start + pr.n_tokens)
+        return fail(CT_ERR_SHAPE, "chunk %d starts at position %d, before chunk %d ends (%lld)", c, ch.new_pos_start,
+                    c - 1, (long long)pr.new_pos_start + pr.n_tokens);
+    }
+    any_host |= ch.location == 1;
+    tab.row_start[c] = (int32_t)n_ctx64;
+    tab.new_start[c] = ch.new_pos_start;
+    n_ctx64 += ch.n_tokens;
+    if (n_ctx64 > 0x7fffffff / 2) return fail(CT_ERR_SHAPE, "context too long");
+  }
+  const int32_t n_ctx = (int32_t)n_ctx64;
+  tab.row_start[n_chunks] = n_ctx;
+  if (n_sel > n_ctx) return fail(CT_ERR_SHAPE, "n_sel %d exceeds n_ctx %d", n_sel, n_ctx);
+  if (recompute_ratio >= 0.0) {
+    if (!(recompute_ratio <= 1.0)) return fail(CT_ERR_RATIO, "recompute_ratio %g is above 1", recompute_ratio);
+    int64_t want = (int64_t)floor(recompute_ratio * (double)n_ctx + 1e-9);
+    if (recompute_ratio > 0.0 && want < 1) want = 1;
+    if (want != n_sel)
+      return fail(CT_ERR_RATIO, "n_sel %d but floor(%g * %d) = %lld", n_sel, recompute_ratio, n_ctx, (long long)want);
+  }
+  if (!k_buf || !v_buf) return fail(CT_ERR_NULL, "k_buf and v_buf must be non-NULL");
+  if (n_sel > 0) {
+    if (!hidden || !sel_idx || !wqkv || !attn_out)
+      return fail(CT_ERR_NULL, "hidden, sel_idx, wqkv and attn_out must be non-NULL when n_sel > 0");
+    const size_t need = ct_workspace_bytes(cfg, n_ctx, n_sel);
+    if (workspace == nullptr) return fail(CT_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (workspace_bytes < need) return fail(CT_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    if (((uintptr_t)workspace & 255) != 0) return fail(CT_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  }
+  if (any_host && compute_stream == copy_stream)
+    return fail(CT_ERR_SHAPE, "pinned-host chunks need a copy_stream different from compute_stream");
+
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+  const size_t row_bytes = (size_t)cfg->n_kv_heads * cfg->head_dim * 2;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+
+  // workspace layout: [attention partials][q rows][k rows][v rows]
+  char* ws = static_cast<char*>(workspace);
+  void *q_rows = nullptr, *k_rows = nullptr, *v_rows = nullptr;
+  if (n_sel > 0) {
+    AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
+    size_t off = up(p.ws_bytes);
+    q_rows = ws + off;
+    off += up((size_t)n_sel * cfg->n_q_heads * cfg->head_dim * 2);
+    k_rows = ws + off;
+    off += up((size_t)n_sel * row_bytes);
+    v_rows = ws + off;
+  }
+
+  // Transfer stream: enqueue every pinned-host chunk's copy first so the DMA engine starts
+  // at once; one event per chunk lets the compute stream rotate chunk c as soon as it lands.
+  std::vector<hipEvent_t> landed;
+  hipError_t e;
+  if (any_host) {
+    // the copies write k_buf / v_buf: they must not overtake earlier work of the compute
+    // stream that still reads the buffers (the previous layer's attention)
+    hipEvent_t fence;
+    if ((e = hipEventCreateWithFlags(&fence, hipEventDisableTiming)) != hipSuccess) return hip_fail(e, "hipEventCreate");
+    e = hipEventRecord(fence, cs);
+    if (e == hipSuccess) e = hipStreamWaitEvent(xs, fence, 0);
+    (void)hipEventDestroy(fence);
+    if (e != hipSuccess) return hip_fail(e, "fence compute->copy stream");
+    landed.resize(n_chunks, nullptr);
+    for (int c = 0; c < n_chunks; ++c) {
+      const ct_chunk& ch = chunks[c];
+      if (ch.location != 1) continue;
+      char* kd = static_cast<char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;
+      char* vd = static_cast<char*>(v_buf) + (size_t)tab.row_start[c] * row_bytes;
+      const size_t bytes = (size_t)ch.n_tokens * row_bytes;
+      e = hipMemcpyAsync(kd, ch.k, bytes, hipMemcpyHostToDevice, xs);
+      if (e == hipSuccess) e = hipMemcpyAsync(vd, ch.v, bytes, hipMemcpyHostToDevice, xs);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&landed[c], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventRecord(landed[c], xs);
+      if (e != hipSuccess) {
+        for (hipEvent_t ev : landed)
+          if (ev) (void)hipEventDestroy(ev);
+        return hip_fail(e, "host->device chunk copy");
+      }
+    }
+  }
+  auto drop_events = [&]() {
+    for (hipEvent_t ev : landed)
+      if (ev) (void)hipEventDestroy(ev);   // destroying a recorded event is deferred by the runtime
+  };
+
+  // Recompute stream: projection of the selected rows runs while the copies are in flight.
+  if (n_sel > 0) {
+    st = launch_qkv(cfg, hidden, hidden_rows, nullptr, sel_idx, &tab, n_sel, wqkv, bias, q_rows, k_rows, v_rows, cs);
+    if (st != CT_OK) {
+      drop_events();
+      return st;
+    }
+  }
+  // Device-resident chunks: rotated (and their values copied) into place in as few launches
+  // as the table size allows; they do not wait for any copy.
+  {
+    ReropeChunks rc;
+    auto flush = [&]() -> ct_status {
+      if (rc.n == 0) return CT_OK;
+      rc.tok_start[rc.n] = rc.total_tokens;
+      ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, cs);
+      rc.n = 0;
+      rc.total_tokens = 0;
+      return r;
+    };
+    memset(&rc, 0, sizeof(rc));
+    for (int c = 0; c < n_chunks; ++c) {
+      const ct_chunk& ch = chunks[c];
+      if (ch.location != 0) continue;
+      const char* kd = static_cast<const char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;
+      const char* vd = static_cast<const char*>(v_buf) + (size_t)tab.row_start[c] * row_bytes;
+      const int i = rc.n++;
+      rc.tok_start[i] = rc.total_tokens;
+      rc.total_tokens += ch.n_tokens;
+      rc.k_src[i] = ch.k;
+      rc.v_src[i] = (ch.v == (const void*)vd) ? nullptr : ch.v;   // already in place: leave the values
+      (void)kd;
+      rc.row_start[i] = tab.row_start[c];
+      rc.delta0[i] = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
+      rc.delta_step[i] = ch.raw_keys ? 1 : 0;
+      if (rc.n == 32 && (st = flush()) != CT_OK) {
+        drop_events();
+        return st;
+      }
+    }
+    if ((st = flush()) != CT_OK) {
+      drop_events();
+      return st;
+    }
+  }
+  // Pinned-host chunks: rotate chunk c in place as soon as its copy has landed.
+  for (int c = 0; c < n_chunks; ++c) {
+    const ct_chunk& ch = chunks[c];
+    if (ch.location != 1) continue;
+    char* kd = static_cast<char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;
+    e = hipStreamWaitEvent(cs, landed[c], 0);
+    if (e != hipSuccess) {
+      drop_events();
+      return hip_fail(e, "hipStreamWaitEvent (chunk landed)");
+    }
+    const int32_t d0 = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
+    st = launch_rerope(cfg, kd, kd, nullptr, nullptr, nullptr, nullptr, d0, ch.raw_keys ? 1 : 0, ch.n_tokens, cs);
+    if (st != CT_OK) {
+      drop_events();
+      return st;
+    }
+  }
+  drop_events();
+  if (n_sel == 0) return CT_OK;
+  st = launch_scatter(cfg, k_buf, v_buf, k_rows, v_rows, sel_idx, n_sel, cs);
+  if (st != CT_OK) return st;
+  return launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs);
+}
+
+}  // extern "C"

@@ -1,0 +1,111 @@
+// Internal declarations shared by the translation units of libcachetune (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cachetune.h"
+
+namespace ct {
+
+// ---- kernel classes for the opt-in event profiling ------------------------------------
+enum KernelClass { KC_QKV = 0, KC_REROPE = 1, KC_SCATTER = 2, KC_ATTN = 3, KC_MERGE = 4, KC_COUNT = 5 };
+
+ct_status fail(ct_status code, const char* fmt, ...);
+ct_status hip_fail(hipError_t e, const char* what);
+ct_status check_cfg(const ct_layer_cfg* cfg);
+
+// Bracket a launch with events when profiling is on.  `begin` returns a slot (or -1).
+int prof_begin(KernelClass kc, hipStream_t s);
+void prof_end(KernelClass kc, int slot, hipStream_t s);
+
+// RoPE frequencies in turns: omega_j / (2 pi), j < head_dim / 2 <= 64, computed on the
+// host in double precision and handed to kernels by value.
+struct RopeTable {
+  double turns[64];
+};
+void fill_rope_table(const ct_layer_cfg* cfg, RopeTable* t);
+
+// Attention launch geometry chosen on the host from the problem size.
+struct AttnPlan {
+  int tile_tokens;   // selected tokens per workgroup tile (256 / group size)
+  int n_tiles;       // ceil(n_sel / tile_tokens)
+  int n_splits;      // key-range splits per tile (1 = no workspace traffic)
+  int split_keys;    // keys per split (multiple of the K tile), meaningful when n_splits > 1
+  size_t ws_bytes;   // workspace bytes needed
+};
+AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel);
+
+// ---- launchers implemented next to their kernels ---------------------------------------
+ct_status launch_rerope(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src, void* v_dst,
+                        const int32_t* old_pos, const int32_t* new_pos, int32_t delta0, int32_t delta_step,
+                        int32_t n_tokens, hipStream_t s);
+// Several device-resident chunks rotated (and their values copied) into the layer buffers
+// in one launch.  v_src[c] == NULL leaves the values of chunk c alone.
+struct ReropeChunks {
+  int32_t n;
+  int32_t pad;
+  int64_t total_tokens;
+  int64_t tok_start[33];   // ordinal of the first token of chunk c among the listed chunks
+  const void* k_src[32];
+  const void* v_src[32];
+  int32_t row_start[32];   // buffer row the chunk's first token goes to
+  int32_t delta0[32];
+  int32_t delta_step[32];
+};
+ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
+                               hipStream_t s);
+ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
+                         const int32_t* sel_idx, int32_t n_sel, hipStream_t s);
+// pos_of_row != NULL: position of selected token s is pos_of_row[s]; otherwise it is looked up
+// through the chunk table (positions of buffer rows) with sel_idx.
+struct ChunkTable {
+  int32_t n;
+  int32_t row_start[65];   // buffer row where chunk c starts; row_start[n] = n_ctx
+  int32_t new_start[64];
+};
+ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
+                     const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
+                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s);
+ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
+                           int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
+                           void* workspace, hipStream_t s);
+
+}  // namespace ct
+
+// ---- device helpers ----------------------------------------------------------------------
+#if defined(__HIPCC__)
+namespace ct {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 p = __builtin_convertvector(v, bf16x2);
+  return *reinterpret_cast<uint32_t*>(&p);
+}
+
+// cos and sin of the angle steps * omega, with omega given in turns (omega / 2pi).
+// The product and its reduction to [-1/2, 1/2] turns are done in fp64, so the angle is good
+// to ~1e-11 rad at any position; the hardware sin/cos take their argument in turns.
+__device__ __forceinline__ void sincos_turns(int32_t steps, double omega_turns, float& c, float& s) {
+  double t = (double)steps * omega_turns;
+  t -= rint(t);
+  float f = (float)t;
+  s = __builtin_amdgcn_sinf(f);
+  c = __builtin_amdgcn_cosf(f);
+}
+
+}  // namespace ct
+#endif

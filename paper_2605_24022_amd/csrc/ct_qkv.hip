@@ -1,0 +1,286 @@
+// Selective recompute of Q, K, V for the selected tokens (Eq. 1) with RoPE at their true
+// positions (Sec. 4.2, last paragraph), as one bf16 MFMA GEMM with a fused epilogue.
+//
+// The kernel computes the transposed product  C^T[f, t] = sum_e W[f, e] * X[row(t), e]
+// (features in the MFMA M dimension, tokens in N) so that, in the 32x32 accumulator layout,
+// a lane holds one token (column) and groups of four consecutive features (rows):
+//   - both elements of every RoPE pair of a token sit in the same lane (no cross-lane
+//     traffic in the epilogue), and the token's position is a per-lane scalar;
+//   - results leave as 8-byte stores of four consecutive bf16 features.
+// Both operands are K-contiguous in memory (W is out-features major, X is token major), so
+// they are staged through LDS with plain 128-bit copies and read back as MFMA fragments
+// with 128-bit LDS reads; rows are padded by 16 bytes to spread the banks.
+//
+// Workgroup: 256 threads = 4 waves (2 x 2), tile 256 features x 128 tokens x 64 (K step),
+// wave tile 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16, double-buffered LDS.
+// Workgroups are numbered so that the ones resident on one XCD (ids congruent mod 8) cover a
+// 4 x 8 patch of tiles and share their W and X tiles in that XCD's L2.
+#include "ct_internal.h"
+
+namespace ct {
+
+namespace {
+
+constexpr int BF = 256;           // features per workgroup
+constexpr int BT = 128;           // tokens per workgroup
+constexpr int BK = 64;            // reduction elements per stage
+constexpr int ROWB = BK * 2 + 16; // padded LDS row in bytes
+constexpr int A_BYTES = BF * ROWB;
+constexpr int B_BYTES = BT * ROWB;
+constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int A_PIECES = BF * BK / 8 / 256;  // 16-byte pieces per thread and stage
+constexpr int B_PIECES = BT * BK / 8 / 256;
+
+struct QkvArgs {
+  const uint16_t* hidden;
+  const int32_t* hidden_rows;
+  const int32_t* sel_pos;
+  const int32_t* sel_idx;
+  const uint16_t* wqkv;
+  const uint16_t* bias;
+  uint16_t* q_out;
+  uint16_t* k_out;
+  uint16_t* v_out;
+  int32_t n_sel, E, O, Hq, Hkv;
+  int32_t nF, nT;
+};
+
+__device__ __forceinline__ int32_t position_of_row(const ChunkTable& tab, int32_t r) {
+  int c = 0;
+  while (c + 1 < tab.n && r >= tab.row_start[c + 1]) ++c;
+  return tab.new_start[c] + (r - tab.row_start[c]);
+}
+
+template <int D, int STYLE>
+__global__ __launch_bounds__(256) void qkv_kernel(QkvArgs a, RopeTable rope, ChunkTable chunks) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hi = lane >> 5;
+
+  // ---- workgroup -> tile, XCD aware (consecutive ids go to different XCDs) ----------------
+  const int total = a.nF * a.nT;
+  const int per_xcd = (total + 7) / 8;
+  const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (v >= total) return;
+  constexpr int PF = 4, PT = 8;
+  const int tp = v / (PT * a.nF);
+  const int rem = v - tp * PT * a.nF;
+  const int th = min(PT, a.nT - tp * PT);
+  const int fp = rem / (PF * th);
+  const int r2 = rem - fp * PF * th;
+  const int fw = min(PF, a.nF - fp * PF);
+  const int f_blk = (fp * PF + r2 % fw) * BF;
+  const int t_blk = (tp * PT + r2 / fw) * BT;
+
+  // ---- global -> LDS staging pointers -------------------------------------------------------
+  const uint16_t* ga[A_PIECES];
+  const uint16_t* gb[B_PIECES];
+  int la[A_PIECES], lb[B_PIECES];
+#pragma unroll
+  for (int i = 0; i < A_PIECES; ++i) {
+    const int p = i * 256 + tid, row = p >> 3, col = p & 7;
+    const int f = min(f_blk + row, a.O - 1);
+    ga[i] = a.wqkv + (size_t)f * a.E + col * 8;
+    la[i] = row * ROWB + col * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < B_PIECES; ++i) {
+    const int p = i * 256 + tid, row = p >> 3, col = p & 7;
+    const int t = min(t_blk + row, a.n_sel - 1);
+    const int64_t xr = a.hidden_rows ? (int64_t)a.hidden_rows[t] : (int64_t)t;
+    gb[i] = a.hidden + xr * a.E + col * 8;
+    lb[i] = A_BYTES + row * ROWB + col * 16;
+  }
+
+  const int wf = wave >> 1, wt = wave & 1;
+  // fragment read offsets inside a stage (bytes)
+  const int a_frag = (wf * 128 + l32) * ROWB + hi * 16;
+  const int b_frag = A_BYTES + (wt * 64 + l32) * ROWB + hi * 16;
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
+
+  u32x4 ra[A_PIECES], rb[B_PIECES];
+  auto load_stage = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < A_PIECES; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + k0);
+#pragma unroll
+    for (int i = 0; i < B_PIECES; ++i) rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + k0);
+  };
+  auto store_stage = [&](int buf) {
+    unsigned char* base = smem + buf * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < A_PIECES; ++i) *reinterpret_cast<u32x4*>(base + la[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_PIECES; ++i) *reinterpret_cast<u32x4*>(base + lb[i]) = rb[i];
+  };
+
+  const int nk = a.E / BK;
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_stage((kt + 1) * BK);
+    const unsigned char* base = smem + buf * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[4], fb[2];
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+        fa[m] = *reinterpret_cast<const bf16x8*>(base + a_frag + m * 32 * ROWB + ks * 32);
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        fb[n] = *reinterpret_cast<const bf16x8*>(base + b_frag + n * 32 * ROWB + ks * 32);
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_stage(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: bias, RoPE, round, store ---------------------------------------------------
+  // accumulator element i of tile (m, n): feature f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
+  const int f0 = f_blk + wf * 128;
+  const int rope_end = (a.Hq + a.Hkv) * D;   // features below this are q or k heads
+  const int q_end = a.Hq * D;
+#pragma unroll
+  for (int n = 0; n < 2; ++n) {
+    const int t = t_blk + wt * 64 + n * 32 + l32;
+    const bool t_ok = t < a.n_sel;
+    const int tc = t_ok ? t : a.n_sel - 1;
+    const int32_t pos = a.sel_pos ? a.sel_pos[tc] : position_of_row(chunks, a.sel_idx[tc]);
+
+    if (a.bias != nullptr) {
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int f = min(f0 + m * 32 + 8 * (i >> 2) + 4 * hi + (i & 3), a.O - 1);
+          acc[m][n][i] += bf16_lo((uint32_t)a.bias[f]);
+        }
+    }
+
+    if (STYLE == 0) {
+      // pairs (j, j + D/2): D = 128 couples tiles (m, m+2); D = 64 couples (m, m+1) for m even
+      constexpr int STEP = D / 64;          // tile distance between the two halves of a pair
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        if ((D == 128 && m >= 2) || (D == 64 && (m & 1))) continue;
+        const int fa0 = f0 + m * 32;        // first feature of the "a" half tile
+        if (fa0 >= rope_end) continue;      // v heads are not rotated
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = (fa0 % D) + 8 * (i >> 2) + 4 * hi + (i & 3);
+          float c, s;
+          sincos_turns(pos, rope.turns[j], c, s);
+          const float x = acc[m][n][i], y = acc[m + STEP][n][i];
+          acc[m][n][i] = x * c - y * s;
+          acc[m + STEP][n][i] = x * s + y * c;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const int fa0 = f0 + m * 32;
+        if (fa0 >= rope_end) continue;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const int j = ((fa0 % D) + 8 * (i >> 2) + 4 * hi + (i & 3)) >> 1;
+          float c, s;
+          sincos_turns(pos, rope.turns[j], c, s);
+          const float x = acc[m][n][i], y = acc[m][n][i + 1];
+          acc[m][n][i] = x * c - y * s;
+          acc[m][n][i + 1] = x * s + y * c;
+        }
+      }
+    }
+
+    if (!t_ok) continue;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const int fm = f0 + m * 32;
+      if (fm >= a.O) continue;
+      uint16_t* dst;
+      if (fm < q_end)
+        dst = a.q_out + (size_t)t * q_end + fm;
+      else if (fm < rope_end)
+        dst = a.k_out + (size_t)t * (a.Hkv * D) + (fm - q_end);
+      else
+        dst = a.v_out + (size_t)t * (a.Hkv * D) + (fm - rope_end);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w;
+        w[0] = pack_bf16(acc[m][n][4 * g + 0], acc[m][n][4 * g + 1]);
+        w[1] = pack_bf16(acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]);
+        *reinterpret_cast<u32x2*>(dst + 8 * g + 4 * hi) = w;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
+                     const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
+                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s) {
+  if (n_sel == 0) return CT_OK;
+  QkvArgs a;
+  a.hidden = static_cast<const uint16_t*>(hidden);
+  a.hidden_rows = hidden_rows;
+  a.sel_pos = sel_pos;
+  a.sel_idx = sel_idx;
+  a.wqkv = static_cast<const uint16_t*>(wqkv);
+  a.bias = static_cast<const uint16_t*>(bias);
+  a.q_out = static_cast<uint16_t*>(q_out);
+  a.k_out = static_cast<uint16_t*>(k_out);
+  a.v_out = static_cast<uint16_t*>(v_out);
+  a.n_sel = n_sel;
+  a.E = cfg->hidden;
+  a.Hq = cfg->n_q_heads;
+  a.Hkv = cfg->n_kv_heads;
+  a.O = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+  a.nF = (a.O + BF - 1) / BF;
+  a.nT = (n_sel + BT - 1) / BT;
+  RopeTable rope;
+  fill_rope_table(cfg, &rope);
+  ChunkTable tab;
+  if (chunks != nullptr) {
+    tab = *chunks;
+  } else {
+    tab.n = 1;
+    tab.row_start[0] = 0;
+    tab.row_start[1] = 0x7fffffff;
+    tab.new_start[0] = 0;
+  }
+  const int total = a.nF * a.nT;
+  const int per_xcd = (total + 7) / 8;
+  dim3 grid(per_xcd * 8), block(256);
+  const size_t shmem = 2 * STAGE_BYTES;
+  auto launch = [&](auto kernel) -> hipError_t {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)shmem);
+    if (e != hipSuccess) return e;
+    int slot = prof_begin(KC_QKV, s);
+    hipLaunchKernelGGL(kernel, grid, block, shmem, s, a, rope, tab);
+    prof_end(KC_QKV, slot, s);
+    return hipGetLastError();
+  };
+  hipError_t e;
+  if (cfg->head_dim == 128)
+    e = cfg->rope_style == 0 ? launch(qkv_kernel<128, 0>) : launch(qkv_kernel<128, 1>);
+  else
+    e = cfg->rope_style == 0 ? launch(qkv_kernel<64, 0>) : launch(qkv_kernel<64, 1>);
+  if (e != hipSuccess) return hip_fail(e, "qkv kernel launch");
+  return CT_OK;
+}
+
+}  // namespace ct

@@ -1,0 +1,247 @@
+// Bandwidth-bound steps of the partial-prefill layer: deferred RoPE recovery of reused keys
+// (Eq. 8, delta form) and scatter fusion of recomputed K/V rows (Sec. 4.2).
+//
+// Both kernels move every byte exactly once with 128-bit accesses.  Key rows are
+// [n_kv_heads, head_dim] bf16; a thread owns 8 rotation pairs of one token and walks over
+// all KV heads, so the 8 sin/cos values (angle reduced in fp64) are computed once per
+// token and pair and reused for every head.
+#include "ct_internal.h"
+
+namespace ct {
+
+namespace {
+
+constexpr int kReropeThreads = 256;
+
+// Rotate (and optionally copy V for) one token's share owned by this thread.
+// STYLE 0: pairs (j, j + D/2); STYLE 1: pairs (2j, 2j + 1).  HEADS > 0 fixes the head count
+// at compile time (full unroll, all loads in flight before the first use).
+// k_src/k_dst (and v_src/v_dst) may be the same row: a thread reads all it owns before it
+// writes, and no two threads own the same bytes.
+template <int D, int STYLE, int HEADS>
+__device__ __forceinline__ void rerope_token(const uint16_t* k_src, uint16_t* k_dst, const uint16_t* v_src,
+                                             uint16_t* v_dst, int32_t delta, int jg, int n_heads_rt,
+                                             const RopeTable& table) {
+  const int n_heads = HEADS > 0 ? HEADS : n_heads_rt;
+  float cs[8], sn[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sincos_turns(delta, table.turns[jg * 8 + i], cs[i], sn[i]);
+
+  // element offsets (in bf16) of the two 16-byte pieces this thread owns inside a head row
+  const int off_a = STYLE == 0 ? jg * 8 : jg * 16;
+  const int off_b = STYLE == 0 ? jg * 8 + D / 2 : jg * 16 + 8;
+
+  auto rotate_head = [&](u32x4 a, u32x4 b, u32x4& ra, u32x4& rb) {
+    if (STYLE == 0) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        float a0 = bf16_lo(a[w]), a1 = bf16_hi(a[w]);
+        float b0 = bf16_lo(b[w]), b1 = bf16_hi(b[w]);
+        float c0 = cs[2 * w], s0 = sn[2 * w], c1 = cs[2 * w + 1], s1 = sn[2 * w + 1];
+        ra[w] = pack_bf16(a0 * c0 - b0 * s0, a1 * c1 - b1 * s1);
+        rb[w] = pack_bf16(a0 * s0 + b0 * c0, a1 * s1 + b1 * c1);
+      }
+    } else {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        float x = bf16_lo(a[w]), y = bf16_hi(a[w]);
+        ra[w] = pack_bf16(x * cs[w] - y * sn[w], x * sn[w] + y * cs[w]);
+        float x2 = bf16_lo(b[w]), y2 = bf16_hi(b[w]);
+        rb[w] = pack_bf16(x2 * cs[4 + w] - y2 * sn[4 + w], x2 * sn[4 + w] + y2 * cs[4 + w]);
+      }
+    }
+  };
+
+  if (HEADS > 0) {
+    u32x4 a[HEADS > 0 ? HEADS : 1], b[HEADS > 0 ? HEADS : 1];
+#pragma unroll
+    for (int h = 0; h < HEADS; ++h) {
+      a[h] = *reinterpret_cast<const u32x4*>(k_src + h * D + off_a);
+      b[h] = *reinterpret_cast<const u32x4*>(k_src + h * D + off_b);
+    }
+#pragma unroll
+    for (int h = 0; h < HEADS; ++h) {
+      u32x4 ra, rb;
+      rotate_head(a[h], b[h], ra, rb);
+      *reinterpret_cast<u32x4*>(k_dst + h * D + off_a) = ra;
+      *reinterpret_cast<u32x4*>(k_dst + h * D + off_b) = rb;
+    }
+    if (v_src != nullptr) {
+#pragma unroll
+      for (int h = 0; h < HEADS; ++h) {
+        a[h] = *reinterpret_cast<const u32x4*>(v_src + h * D + off_a);
+        b[h] = *reinterpret_cast<const u32x4*>(v_src + h * D + off_b);
+      }
+#pragma unroll
+      for (int h = 0; h < HEADS; ++h) {
+        *reinterpret_cast<u32x4*>(v_dst + h * D + off_a) = a[h];
+        *reinterpret_cast<u32x4*>(v_dst + h * D + off_b) = b[h];
+      }
+    }
+  } else {
+    for (int h = 0; h < n_heads; ++h) {
+      u32x4 a = *reinterpret_cast<const u32x4*>(k_src + h * D + off_a);
+      u32x4 b = *reinterpret_cast<const u32x4*>(k_src + h * D + off_b);
+      u32x4 ra, rb;
+      rotate_head(a, b, ra, rb);
+      *reinterpret_cast<u32x4*>(k_dst + h * D + off_a) = ra;
+      *reinterpret_cast<u32x4*>(k_dst + h * D + off_b) = rb;
+      if (v_src != nullptr) {
+        u32x4 va = *reinterpret_cast<const u32x4*>(v_src + h * D + off_a);
+        u32x4 vb = *reinterpret_cast<const u32x4*>(v_src + h * D + off_b);
+        *reinterpret_cast<u32x4*>(v_dst + h * D + off_a) = va;
+        *reinterpret_cast<u32x4*>(v_dst + h * D + off_b) = vb;
+      }
+    }
+  }
+}
+
+// Per-token positions, or one arithmetic progression of deltas (delta0 + delta_step * t).
+template <int D, int STYLE, int HEADS>
+__global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
+    const uint16_t* k_src, uint16_t* k_dst, const uint16_t* v_src, uint16_t* v_dst,
+    const int32_t* __restrict__ old_pos, const int32_t* __restrict__ new_pos, int32_t delta0, int32_t delta_step,
+    int32_t n_tokens, int32_t n_heads_rt, RopeTable table) {
+  constexpr int GROUPS = D / 16;  // threads per token: each owns 8 pairs = 16 elements per head
+  const int64_t gid = (int64_t)blockIdx.x * kReropeThreads + threadIdx.x;
+  const int64_t token = gid / GROUPS;
+  const int jg = (int)(gid % GROUPS);
+  if (token >= n_tokens) return;
+  int32_t delta;
+  if (new_pos != nullptr) {
+    delta = new_pos[token] - (old_pos != nullptr ? old_pos[token] : 0);
+  } else {
+    delta = delta0 + delta_step * (int32_t)token;
+  }
+  const int64_t row = token * (int64_t)(HEADS > 0 ? HEADS : n_heads_rt) * D;
+  rerope_token<D, STYLE, HEADS>(k_src + row, k_dst + row, v_src ? v_src + row : nullptr,
+                                v_dst ? v_dst + row : nullptr, delta, jg, n_heads_rt, table);
+}
+
+// Several chunks in one launch: buffer row -> chunk by search in the (small) table.
+template <int D, int STYLE, int HEADS>
+__global__ __launch_bounds__(kReropeThreads) void rerope_chunks_kernel(uint16_t* k_buf, uint16_t* v_buf,
+                                                                      int32_t n_heads_rt, RopeTable table,
+                                                                      ReropeChunks chunks) {
+  constexpr int GROUPS = D / 16;
+  const int64_t gid = (int64_t)blockIdx.x * kReropeThreads + threadIdx.x;
+  const int64_t t_all = gid / GROUPS;      // ordinal among the tokens of the listed chunks
+  const int jg = (int)(gid % GROUPS);
+  if (t_all >= chunks.total_tokens) return;
+  int c = 0;
+  while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
+  const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
+  const int64_t heads = HEADS > 0 ? HEADS : n_heads_rt;
+  const int64_t src_row = (int64_t)t * heads * D;
+  const int64_t dst_row = ((int64_t)chunks.row_start[c] + t) * heads * D;
+  const uint16_t* ks = static_cast<const uint16_t*>(chunks.k_src[c]) + src_row;
+  const uint16_t* vs = chunks.v_src[c] ? static_cast<const uint16_t*>(chunks.v_src[c]) + src_row : nullptr;
+  const int32_t delta = chunks.delta0[c] + chunks.delta_step[c] * t;
+  rerope_token<D, STYLE, HEADS>(ks, k_buf + dst_row, vs, v_buf + dst_row, delta, jg, n_heads_rt, table);
+}
+
+// One 16-byte piece per thread and loop step; a selected row's K and V are `row_vec`
+// pieces each.  Pieces of consecutive threads are consecutive in memory.
+__global__ __launch_bounds__(256) void scatter_kernel(u32x4* __restrict__ k_buf, u32x4* __restrict__ v_buf,
+                                                     const u32x4* __restrict__ k_sel,
+                                                     const u32x4* __restrict__ v_sel,
+                                                     const int32_t* __restrict__ sel_idx, int32_t n_sel,
+                                                     int32_t row_vec) {
+  const int64_t total = (int64_t)n_sel * row_vec;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t s = p / row_vec;
+    const int c = (int)(p - s * row_vec);
+    const int64_t dst = (int64_t)sel_idx[s] * row_vec + c;
+    u32x4 kv = k_sel[p];
+    u32x4 vv = v_sel[p];
+    k_buf[dst] = kv;
+    v_buf[dst] = vv;
+  }
+}
+
+template <int D, int STYLE, int HEADS>
+void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* kd, const uint16_t* vs, uint16_t* vd,
+                       const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep, int32_t n, int H,
+                       const RopeTable& t, const ReropeChunks* chunks) {
+  if (chunks != nullptr) {
+    hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
+                       *chunks);
+  } else {
+    hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op, np, d0,
+                       dstep, n, H, t);
+  }
+}
+
+template <int D, int STYLE>
+void launch_rerope_heads(int H, dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* kd, const uint16_t* vs,
+                         uint16_t* vd, const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep, int32_t n,
+                         const RopeTable& t, const ReropeChunks* chunks) {
+  if (H == 8)
+    launch_rerope_one<D, STYLE, 8>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks);
+  else if (H == 2)
+    launch_rerope_one<D, STYLE, 2>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks);
+  else
+    launch_rerope_one<D, STYLE, 0>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks);
+}
+
+ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_t* kd, const uint16_t* vs,
+                            uint16_t* vd, const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep,
+                            int64_t n_tokens, const ReropeChunks* chunks, hipStream_t s) {
+  if (n_tokens == 0) return CT_OK;
+  RopeTable table;
+  fill_rope_table(cfg, &table);
+  const int D = cfg->head_dim, H = cfg->n_kv_heads;
+  const int64_t threads = n_tokens * (D / 16);
+  dim3 grid((unsigned)((threads + kReropeThreads - 1) / kReropeThreads));
+  int slot = prof_begin(KC_REROPE, s);
+  if (D == 128) {
+    if (cfg->rope_style == 0)
+      launch_rerope_heads<128, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+    else
+      launch_rerope_heads<128, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+  } else {
+    if (cfg->rope_style == 0)
+      launch_rerope_heads<64, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+    else
+      launch_rerope_heads<64, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+  }
+  prof_end(KC_REROPE, slot, s);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, "re-RoPE kernel launch");
+  return CT_OK;
+}
+
+}  // namespace
+
+ct_status launch_rerope(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src, void* v_dst,
+                        const int32_t* old_pos, const int32_t* new_pos, int32_t delta0, int32_t delta_step,
+                        int32_t n_tokens, hipStream_t s) {
+  return launch_rerope_any(cfg, static_cast<const uint16_t*>(k_src), static_cast<uint16_t*>(k_dst),
+                           static_cast<const uint16_t*>(v_src), static_cast<uint16_t*>(v_dst), old_pos, new_pos,
+                           delta0, delta_step, n_tokens, nullptr, s);
+}
+
+ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
+                               hipStream_t s) {
+  return launch_rerope_any(cfg, nullptr, static_cast<uint16_t*>(k_buf), nullptr, static_cast<uint16_t*>(v_buf),
+                           nullptr, nullptr, 0, 0, chunks->total_tokens, chunks, s);
+}
+
+ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
+                         const int32_t* sel_idx, int32_t n_sel, hipStream_t s) {
+  if (n_sel == 0) return CT_OK;
+  const int row_vec = cfg->n_kv_heads * cfg->head_dim / 8;  // 16-byte pieces per row
+  const int64_t total = (int64_t)n_sel * row_vec;
+  int64_t blocks = (total + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  int slot = prof_begin(KC_SCATTER, s);
+  hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<u32x4*>(k_buf),
+                     static_cast<u32x4*>(v_buf), static_cast<const u32x4*>(k_sel), static_cast<const u32x4*>(v_sel),
+                     sel_idx, n_sel, row_vec);
+  prof_end(KC_SCATTER, slot, s);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, "scatter kernel launch");
+  return CT_OK;
+}
+
+}  // namespace ct

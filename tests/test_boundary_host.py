@@ -1,0 +1,144 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares and
+rejects bad arguments before it touches HIP."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_24022_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-NULL address that is never dereferenced by validation
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load()
+
+
+def _cfg(**kw):
+    base = dict(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, rope_theta=5e5)
+    base.update(kw)
+    return B.make_cfg(**base)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(os.path.join(ROOT, "include", "cachetune.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ct_[a-z_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.ct_version().startswith("cachetune-gfx950")
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.LayerCfg) == 32
+    assert ctypes.sizeof(B.Chunk) == 40
+
+
+def _status(fn, *args, **kw):
+    with pytest.raises(B.CacheTuneError) as ei:
+        fn(*args, **kw)
+    assert ei.value.message
+    return ei.value.status
+
+
+def test_cfg_validation():
+    for bad, want in [(dict(head_dim=96), B.CT_ERR_UNSUPPORTED), (dict(n_q_heads=30), B.CT_ERR_SHAPE),
+                      (dict(n_q_heads=24, n_kv_heads=8), B.CT_ERR_UNSUPPORTED), (dict(hidden=100), B.CT_ERR_UNSUPPORTED),
+                      (dict(rope_style=2), B.CT_ERR_UNSUPPORTED), (dict(rope_theta=0.0), B.CT_ERR_SHAPE),
+                      (dict(hidden=0), B.CT_ERR_SHAPE)]:
+        st = _status(B.ct_rerope_keys, _cfg(**bad), FAKE, FAKE, None, FAKE, 16)
+        assert st == want, (bad, st)
+    assert B.ct_workspace_bytes(_cfg(head_dim=96), 1024, 10) == 0
+
+
+def test_null_and_shape_errors():
+    c = _cfg()
+    assert _status(B.ct_rerope_keys, c, None, FAKE, None, FAKE, 16) == B.CT_ERR_NULL
+    assert _status(B.ct_rerope_keys, c, FAKE, FAKE, None, None, 16) == B.CT_ERR_NULL
+    assert _status(B.ct_rerope_keys, c, FAKE, FAKE, None, FAKE, -1) == B.CT_ERR_SHAPE
+    assert _status(B.ct_rerope_chunk, c, FAKE, FAKE, FAKE, None, 16, 0, 0) == B.CT_ERR_NULL
+    assert _status(B.ct_scatter_kv, c, FAKE, None, 64, FAKE, FAKE, FAKE, 4) == B.CT_ERR_NULL
+    assert _status(B.ct_scatter_kv, c, FAKE, FAKE, 4, FAKE, FAKE, FAKE, 8) == B.CT_ERR_SHAPE
+    assert _status(B.ct_qkv_selected, c, FAKE, None, None, 4, FAKE, None, FAKE, FAKE, FAKE) == B.CT_ERR_NULL
+    assert _status(B.ct_qkv_selected, c, FAKE, None, FAKE, -4, FAKE, None, FAKE, FAKE, FAKE) == B.CT_ERR_SHAPE
+    assert _status(B.ct_selected_attention, c, FAKE, FAKE, FAKE, 0, FAKE, 4, FAKE, None, None, 0) == B.CT_ERR_SHAPE
+    assert _status(B.ct_selected_attention, c, None, FAKE, FAKE, 64, FAKE, 4, FAKE, None, None, 0) == B.CT_ERR_NULL
+    # empty work is legal and needs no GPU
+    B.ct_rerope_keys(c, None, None, None, None, 0)
+    B.ct_scatter_kv(c, None, None, 64, None, None, None, 0)
+    B.ct_qkv_selected(c, None, None, None, 0, None, None, None, None, None)
+    B.ct_selected_attention(c, None, None, None, 64, None, 0, None, None, None, 0)
+
+
+def test_attention_workspace_checks():
+    c = _cfg()
+    need = B.ct_workspace_bytes(c, 32768, 1638)   # few tiles -> split keys -> partials in the workspace
+    assert need > 0
+    assert _status(B.ct_selected_attention, c, FAKE, FAKE, FAKE, 32768, FAKE, 1638, FAKE, None, None, 0) \
+        == B.CT_ERR_WORKSPACE
+    assert _status(B.ct_selected_attention, c, FAKE, FAKE, FAKE, 32768, FAKE, 1638, FAKE, None, FAKE, 1024) \
+        == B.CT_ERR_WORKSPACE
+    assert _status(B.ct_selected_attention, c, FAKE, FAKE, FAKE, 32768, FAKE, 1638, FAKE, None, FAKE + 8, need) \
+        == B.CT_ERR_WORKSPACE
+
+
+def _chunks(n=4, length=256, **kw):
+    return B.make_chunks([dict(k=FAKE, v=FAKE, n_tokens=length, old_pos_start=0, new_pos_start=i * length, **kw)
+                          for i in range(n)])
+
+
+def test_layer_validation():
+    c = B.make_cfg(512, 8, 2, 64, 1e4)
+    ch = _chunks()
+    args = dict(hidden=FAKE, hidden_rows=None, sel_idx=FAKE, n_sel=153, recompute_ratio=0.15, wqkv=FAKE, bias=None,
+                k_buf=FAKE, v_buf=FAKE, attn_out=FAKE, workspace=None, workspace_bytes=0)
+
+    def call(chunks=ch, n_chunks=4, **over):
+        a = dict(args); a.update(over)
+        return _status(B.ct_partial_prefill_layer, c, chunks, n_chunks, a["hidden"], a["hidden_rows"], a["sel_idx"],
+                       a["n_sel"], a["recompute_ratio"], a["wqkv"], a["bias"], a["k_buf"], a["v_buf"],
+                       a["attn_out"], a["workspace"], a["workspace_bytes"])
+
+    assert call(n_sel=150) == B.CT_ERR_RATIO                 # floor(0.15 * 1024) = 153
+    assert call(recompute_ratio=1.5) == B.CT_ERR_RATIO
+    assert call() == B.CT_ERR_WORKSPACE                      # ratio fine, workspace missing
+    assert call(recompute_ratio=-1.0, n_sel=150) == B.CT_ERR_WORKSPACE   # negative ratio disables the check
+    assert call(n_chunks=0) == B.CT_ERR_SHAPE
+    assert call(n_chunks=65) == B.CT_ERR_UNSUPPORTED
+    assert call(n_sel=2000, recompute_ratio=-1.0) == B.CT_ERR_SHAPE
+    assert call(k_buf=None) == B.CT_ERR_NULL
+    assert call(hidden=None, workspace=FAKE, workspace_bytes=1 << 30) == B.CT_ERR_NULL
+    bad = _chunks(); bad[2].new_pos_start = 100              # overlaps chunk 1 in position
+    assert call(chunks=bad) == B.CT_ERR_SHAPE
+    bad = _chunks(); bad[1].n_tokens = 0
+    assert call(chunks=bad) == B.CT_ERR_SHAPE
+    bad = _chunks(); bad[3].k = None
+    assert call(chunks=bad) == B.CT_ERR_NULL
+    host = _chunks(location=1)                               # pinned-host chunks need a second stream
+    need = B.ct_workspace_bytes(c, 1024, 153)
+    assert call(chunks=host, workspace=FAKE, workspace_bytes=need) == B.CT_ERR_SHAPE
+
+
+def test_validate_indices():
+    good = np.array([0, 3, 4, 9], dtype=np.int32)
+    B.ct_validate_indices(good, 4, 10)
+    B.ct_validate_indices(None, 0, 10)
+    for bad in ([0, 3, 3, 9], [0, 5, 4, 9], [-1, 3, 4, 9], [0, 3, 4, 10]):
+        assert _status(B.ct_validate_indices, np.array(bad, dtype=np.int32), 4, 10) == B.CT_ERR_INDEX
+    assert _status(B.ct_validate_indices, good, 4, 3) == B.CT_ERR_SHAPE
+    assert _status(B.ct_validate_indices, None, 4, 10) == B.CT_ERR_NULL
+
+
+def test_workspace_size_grows_with_problem():
+    c = _cfg()
+    small = B.ct_workspace_bytes(c, 8192, 1228)
+    big = B.ct_workspace_bytes(c, 32768, 4915)
+    assert 0 < small < big
+    # q, k, v staging of the layer call must fit
+    assert big >= 4915 * (32 + 16) * 128 * 2

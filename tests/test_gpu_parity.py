@@ -1,0 +1,276 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs.  Acceptance: bit-exact for scatter placement and copies;
+max-abs <= 2e-2 and per-row relative L2 <= 1e-2 for bf16-in / fp32-accumulate outputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ct_oracle as O
+from paper_2605_24022_amd import binding as B
+from paper_2605_24022_amd import workloads as W
+from tests.gpu_util import (assert_close, bits_of, dev_bf16, dev_i32, f64_of, pinned_bf16, say)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU (run with -m 'not gpu' elsewhere)"
+    B.load()
+    torch.cuda.set_device(0)
+
+
+def _shape(E, Hq, Hkv, D, theta, style=0):
+    return W.LayerShape(E, Hq, Hkv, D, theta, style)
+
+
+# ------------------------------------------------------------------------------ re-RoPE
+@pytest.mark.parametrize("Hkv,D,theta,style", [(2, 64, 1e4, 0), (8, 128, 5e5, 0), (8, 128, 5e5, 1), (3, 64, 1e4, 1),
+                                                 (4, 128, 1e4, 0)])
+def test_rerope_per_token_positions(Hkv, D, theta, style):
+    n = 1000 + 37                                    # ragged: not a multiple of the block's tokens
+    rng = np.random.default_rng([11, Hkv, D, style])
+    k_bits = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, D), dtype=np.float32))
+    old = rng.integers(0, 4096, n).astype(np.int32)
+    new = rng.integers(0, 131072, n).astype(np.int32)   # deltas of either sign, up to 1.3e5
+    new[:4] = old[:4]                                 # delta 0 must be the identity
+    cfg = B.make_cfg(Hkv * D * 2, Hkv * 2, Hkv, D, theta, style)
+    say(f"rerope per-token Hkv={Hkv} D={D} style={style} n={n}")
+    k = dev_bf16(k_bits)
+    out = torch.empty_like(k)
+    B.ct_rerope_keys(cfg, k, out, dev_i32(old), dev_i32(new), n)
+    torch.cuda.synchronize()
+    want = O.rerope_keys(W.bf16_bits_to_f64(k_bits), old, new, theta, style)
+    assert_close(f64_of(out), want, "rerope src->dst", rel_l2=2.5e-3)
+    assert np.array_equal(bits_of(out)[:4], k_bits[:4])
+    # in place, and old_pos = NULL means a raw (never rotated) cache
+    B.ct_rerope_keys(cfg, k, k, None, dev_i32(new), n)
+    torch.cuda.synchronize()
+    want0 = O.rerope_keys(W.bf16_bits_to_f64(k_bits), np.zeros(n, dtype=np.int64), new, theta, style)
+    assert_close(f64_of(k), want0, "rerope in place, raw cache", rel_l2=2.5e-3)
+
+
+@pytest.mark.parametrize("raw", [0, 1])
+def test_rerope_chunk_with_value_copy(raw):
+    Hkv, D, theta, n = 8, 128, 5e5, 513
+    rng = np.random.default_rng([12, raw])
+    k_bits = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, D), dtype=np.float32))
+    v_bits = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, D), dtype=np.float32))
+    cfg = B.make_cfg(4096, 32, Hkv, D, theta)
+    old0, new0 = 7, 100000
+    say(f"rerope chunk raw={raw}")
+    k, v = dev_bf16(k_bits), dev_bf16(v_bits)
+    ko, vo = torch.zeros_like(k), torch.zeros_like(v)
+    B.ct_rerope_chunk(cfg, k, ko, v, vo, n, old0, new0, raw)
+    torch.cuda.synchronize()
+    t = np.arange(n)
+    old = np.zeros(n, dtype=np.int64) if raw else old0 + t
+    want = O.rerope_keys(W.bf16_bits_to_f64(k_bits), old, new0 + t, theta)
+    assert_close(f64_of(ko), want, "rerope chunk", rel_l2=2.5e-3)
+    assert np.array_equal(bits_of(vo), v_bits)
+
+
+# ------------------------------------------------------------------------------ scatter
+@pytest.mark.parametrize("Hkv,D", [(2, 64), (8, 128)])
+def test_scatter_bit_exact(Hkv, D):
+    n_ctx, n_sel = 3001, 457
+    rng = np.random.default_rng([13, Hkv])
+    kb = rng.integers(0, 65536, (n_ctx, Hkv, D)).astype(np.uint16)     # any bit pattern, NaNs included
+    vb = rng.integers(0, 65536, (n_ctx, Hkv, D)).astype(np.uint16)
+    ks = rng.integers(0, 65536, (n_sel, Hkv, D)).astype(np.uint16)
+    vs = rng.integers(0, 65536, (n_sel, Hkv, D)).astype(np.uint16)
+    sel = np.sort(rng.choice(n_ctx, n_sel, replace=False)).astype(np.int32)
+    sel[0], sel[-1] = 0, n_ctx - 1
+    sel = np.unique(sel).astype(np.int32)
+    n_sel = sel.size
+    ks, vs = ks[:n_sel], vs[:n_sel]
+    cfg = B.make_cfg(Hkv * D * 2, Hkv * 2, Hkv, D, 1e4)
+    say(f"scatter Hkv={Hkv} D={D}")
+    k, v = dev_bf16(kb), dev_bf16(vb)
+    B.ct_scatter_kv(cfg, k, v, n_ctx, dev_bf16(ks), dev_bf16(vs), dev_i32(sel), n_sel)
+    torch.cuda.synchronize()
+    k_want, v_want = O.scatter_kv(kb, vb, ks, vs, sel)
+    assert np.array_equal(bits_of(k), k_want)
+    assert np.array_equal(bits_of(v), v_want)
+
+
+# ------------------------------------------------------------------------------ QKV projection
+@pytest.mark.parametrize("E,Hq,Hkv,D,theta,style,n_rows,n_sel,bias", [
+    (512, 8, 2, 64, 1e4, 0, 1024, 153, False),       # config-1 shape
+    (512, 8, 2, 64, 1e4, 1, 300, 300, True),         # interleaved pairs, bias, all rows
+    (1024, 8, 2, 128, 5e5, 0, 700, 333, True),       # ragged tile tails
+    (1024, 6, 3, 64, 1e4, 0, 400, 129, False),       # odd head counts: k/v boundary inside a 128-feature tile
+    (4096, 32, 8, 128, 5e5, 0, 600, 257, False),     # Llama-3-8B layer shape
+])
+def test_qkv_selected(E, Hq, Hkv, D, theta, style, n_rows, n_sel, bias):
+    sh = _shape(E, Hq, Hkv, D, theta, style)
+    rng = np.random.default_rng([14, E, Hq, n_sel])
+    hid = W.f32_to_bf16_bits(rng.standard_normal((n_rows, E), dtype=np.float32))
+    wq = W.f32_to_bf16_bits(rng.standard_normal((sh.qkv_width, E), dtype=np.float32) / np.float32(math.sqrt(E)))
+    bs = W.f32_to_bf16_bits(rng.standard_normal(sh.qkv_width, dtype=np.float32) * np.float32(0.5)) if bias else None
+    rows = np.sort(rng.choice(n_rows, n_sel, replace=False)).astype(np.int32)
+    pos = (rows.astype(np.int64) * 37 + 5).astype(np.int32)           # positions up to ~4e4
+    pos[-1] = 131071
+    cfg = B.cfg_from_shape(sh)
+    say(f"qkv E={E} Hq={Hq} Hkv={Hkv} D={D} style={style} n_sel={n_sel} bias={bias}")
+    q = torch.zeros((n_sel, Hq, D), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((n_sel, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    v = torch.zeros((n_sel, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    B.ct_qkv_selected(cfg, dev_bf16(hid), dev_i32(rows), dev_i32(pos), n_sel, dev_bf16(wq),
+                      None if bs is None else dev_bf16(bs), q, k, v)
+    torch.cuda.synchronize()
+    qw, kw, vw = O.qkv_selected(W.bf16_bits_to_f64(hid[rows]), W.bf16_bits_to_f64(wq),
+                                None if bs is None else W.bf16_bits_to_f64(bs), pos, Hq, Hkv, D, theta, style)
+    assert_close(f64_of(q), qw, "q")
+    assert_close(f64_of(k), kw, "k")
+    assert_close(f64_of(v), vw, "v")
+    # compact hidden (hidden_rows = NULL) gives the same bits
+    q2, k2, v2 = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+    B.ct_qkv_selected(cfg, dev_bf16(hid[rows]), None, dev_i32(pos), n_sel, dev_bf16(wq),
+                      None if bs is None else dev_bf16(bs), q2, k2, v2)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2) and torch.equal(k, k2) and torch.equal(v, v2)
+
+
+# ------------------------------------------------------------------------------ selected attention
+def _attention_case(Hq, Hkv, D, n_ctx, sel, seed, rows=None, want_split=None):
+    rng = np.random.default_rng([15, seed])
+    n_sel = sel.size
+    qb = W.f32_to_bf16_bits(rng.standard_normal((n_sel, Hq, D), dtype=np.float32))
+    kb = W.f32_to_bf16_bits(rng.standard_normal((n_ctx, Hkv, D), dtype=np.float32))
+    vb = W.f32_to_bf16_bits(rng.standard_normal((n_ctx, Hkv, D), dtype=np.float32))
+    cfg = B.make_cfg(Hq * D, Hq, Hkv, D, 1e4)
+    ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    say(f"attention Hq={Hq} Hkv={Hkv} D={D} n_ctx={n_ctx} n_sel={n_sel} ws={ws_bytes}")
+    out = torch.full((n_sel, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((n_sel, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    B.ct_selected_attention(cfg, dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), n_ctx, dev_i32(sel), n_sel, out, lse,
+                            ws, ws_bytes)
+    torch.cuda.synchronize()
+    want, want_lse = O.selected_attention(W.bf16_bits_to_f64(qb), W.bf16_bits_to_f64(kb), W.bf16_bits_to_f64(vb),
+                                          sel, rows=rows)
+    got = f64_of(out)
+    got_lse = lse.cpu().numpy().astype(np.float64)
+    if rows is not None:
+        assert np.isfinite(got).all()
+        got, got_lse = got[rows], got_lse[rows]
+    assert_close(got, want, "attention out")
+    assert np.max(np.abs(got_lse - want_lse)) <= 2e-2, np.max(np.abs(got_lse - want_lse))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,n_ctx,n_sel,seed", [
+    (8, 2, 64, 1024, 153, 1),        # config-1 shape
+    (8, 2, 64, 1000, 1000, 2),       # r = 100 %, ragged key tail (not a multiple of 64)
+    (32, 8, 128, 2048, 307, 3),      # Llama head layout
+    (4, 4, 128, 700, 50, 4),         # G = 1: 256-token tiles
+    (16, 2, 128, 900, 77, 5),        # G = 8: 32-token tiles
+    (32, 8, 128, 777, 1, 6),         # a single selected row
+    (32, 8, 128, 8192, 400, 7),      # few tiles, long context -> key-range splits + merge
+])
+def test_selected_attention(Hq, Hkv, D, n_ctx, n_sel, seed):
+    rng = np.random.default_rng([16, seed])
+    sel = np.arange(n_ctx, dtype=np.int32) if n_sel == n_ctx else \
+        np.sort(rng.choice(n_ctx, n_sel, replace=False)).astype(np.int32)
+    if n_sel > 2:
+        sel[0] = 0                    # a query that sees exactly one key
+        sel = np.unique(sel).astype(np.int32)
+    _attention_case(Hq, Hkv, D, n_ctx, sel, seed)
+
+
+def test_selected_attention_clustered_rows():
+    """Dense runs of selected rows next to sparse ones (the long-context selection pattern)."""
+    n_ctx = 4096
+    sel = np.unique(np.concatenate([np.arange(0, 64), np.arange(1000, 1128), [2000, 3000, 4095]])).astype(np.int32)
+    _attention_case(32, 8, 128, n_ctx, sel, 21)
+
+
+# ------------------------------------------------------------------------------ whole layer
+def _run_layer(wl, pinned=False, poison=True, in_place=False):
+    sp, sh = wl.spec, wl.spec.shape
+    cfg = B.cfg_from_shape(sh)
+    n_ctx, n_sel = sp.n_ctx, sp.n_sel
+    hidden = dev_bf16(wl.hidden)
+    rows = None if wl.hidden_rows is None else dev_i32(wl.hidden_rows)
+    wqkv = dev_bf16(wl.wqkv)
+    sel = dev_i32(wl.sel_idx)
+    k_cache, v_cache = wl.k_cache.copy(), wl.v_cache.copy()
+    if poison:                        # stale K/V at the selected slots must never be read
+        k_cache[wl.sel_idx] = 0x7FC0
+        v_cache[wl.sel_idx] = 0x7FC0
+    fill = float("nan") if poison else 0.0
+    k_buf = torch.full((n_ctx, sh.n_kv_heads, sh.head_dim), fill, dtype=torch.bfloat16, device="cuda")
+    v_buf = torch.full((n_ctx, sh.n_kv_heads, sh.head_dim), fill, dtype=torch.bfloat16, device="cuda")
+    if pinned:
+        k_pool, v_pool = pinned_bf16(k_cache), pinned_bf16(v_cache)
+    elif in_place:
+        k_buf.copy_(dev_bf16(k_cache)); v_buf.copy_(dev_bf16(v_cache))
+        k_pool, v_pool = k_buf, v_buf
+    else:
+        k_pool, v_pool = dev_bf16(k_cache), dev_bf16(v_cache)
+    entries = []
+    for c in range(sp.n_chunks):
+        lo, hi = int(wl.chunk_rows[c]), int(wl.chunk_rows[c + 1])
+        entries.append(dict(k=k_pool[lo:hi], v=v_pool[lo:hi], n_tokens=hi - lo,
+                            old_pos_start=int(wl.chunk_old_start[c]), new_pos_start=int(wl.chunk_new_start[c]),
+                            location=1 if pinned else 0))
+    chunks = B.make_chunks(entries)
+    ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    out = torch.full((n_sel, sh.n_q_heads, sh.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    say(f"layer {sp.name} n_ctx={n_ctx} n_sel={n_sel} pinned={pinned} in_place={in_place} ws={ws_bytes}")
+    B.ct_partial_prefill_layer(cfg, chunks, sp.n_chunks, hidden, rows, sel, n_sel, sp.ratio_pct / 100.0, wqkv, None,
+                               k_buf, v_buf, out, ws, ws_bytes, compute, copy)
+    torch.cuda.synchronize()
+    return out, k_buf, v_buf
+
+
+def _oracle_layer(wl, rows=None):
+    sh = wl.spec.shape
+    hid = W.bf16_bits_to_f64(wl.hidden if wl.hidden_rows is None else wl.hidden[wl.hidden_rows])
+    return O.partial_prefill_layer(hid, W.bf16_bits_to_f64(wl.wqkv), None, W.bf16_bits_to_f64(wl.k_cache),
+                                   W.bf16_bits_to_f64(wl.v_cache), wl.old_pos, wl.new_pos, wl.sel_idx,
+                                   sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta, sh.rope_style, rows=rows)
+
+
+def _check_layer(wl, out, k_buf, v_buf, rows=None):
+    want, _, k_want, v_want = _oracle_layer(wl, rows=rows)
+    got = f64_of(out)
+    assert np.isfinite(got).all(), "a stale or unwritten row leaked into the attention output"
+    assert_close(got if rows is None else got[rows], want, f"{wl.spec.name} attention output")
+    assert_close(f64_of(k_buf), k_want, f"{wl.spec.name} fused K")
+    # reused values are copies, recomputed values are rounded fp32 results
+    reused = np.setdiff1d(np.arange(wl.spec.n_ctx), wl.sel_idx)
+    assert np.array_equal(bits_of(v_buf)[reused], wl.v_cache[reused]), "reused V rows must be bit-exact copies"
+    assert_close(f64_of(v_buf)[wl.sel_idx], v_want[wl.sel_idx], f"{wl.spec.name} recomputed V")
+
+
+@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned"])
+def test_layer_config1(mode):
+    wl = W.make_workload(W.spec(1))
+    out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place")
+    _check_layer(wl, out, kb, vb)
+
+
+@pytest.mark.parametrize("ratio", [100, 0])
+def test_layer_config1_ratio_edges(ratio):
+    """r = 100 % is ordinary full causal prefill; r = 0 is full KV reuse (buffers only)."""
+    sp = W.spec(1, ratio) if ratio else W.custom_spec("cfg1-r0", W.TINY, 4, 256, 0)
+    wl = W.make_workload(sp)
+    out, kb, vb = _run_layer(wl, poison=ratio != 0)
+    if ratio:
+        _check_layer(wl, out, kb, vb)
+    else:
+        k_want = O.rerope_keys(W.bf16_bits_to_f64(wl.k_cache), wl.old_pos, wl.new_pos, sp.shape.rope_theta)
+        assert_close(f64_of(kb), k_want, "full reuse fused K", rel_l2=2.5e-3)
+        assert np.array_equal(bits_of(vb), wl.v_cache)
+
+
+def test_layer_config2():
+    wl = W.make_workload(W.spec(2))
+    out, kb, vb = _run_layer(wl)
+    _check_layer(wl, out, kb, vb)
