@@ -24,6 +24,7 @@
 // Workgroup ids map KV head = id mod n_kv_heads, so with 8 KV heads every XCD streams the
 // keys of one head through its own L2; tiles are issued heaviest first.
 #include <math.h>
+#include <stdlib.h>
 
 #include "ct_internal.h"
 
@@ -32,7 +33,6 @@ namespace ct {
 namespace {
 
 constexpr int BN = 64;                 // keys per LDS tile
-constexpr int VT_ROWB = BN * 2 + 16;   // bytes per head_dim row of V^T in LDS
 
 struct AttnArgs {
   const uint16_t* q;
@@ -47,27 +47,57 @@ struct AttnArgs {
   float scale_log2;   // softmax scale * log2(e)
 };
 
-// value held by lane ^ 32
-__device__ __forceinline__ float lane_xor32(float x) { return __shfl_xor(x, 32); }
+// v_permlane32_swap exchanges the upper half of the first operand with the lower half of
+// the second: with both operands x, result[0] is (x | partner) and result[1] is
+// (partner | x) over (lanes 0-31 | lanes 32-63), so any commutative combination of the two
+// results combines every lane with lane ^ 32.
+__device__ __forceinline__ float max_with_lane_xor32(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_lane_xor32(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// Swizzles of the 16-byte pieces inside a key row of the LDS tiles (rows are unpadded:
+// direct global->LDS loads write 64 lanes x 16 bytes contiguously).  K rows are read one
+// row per lane (ds_read_b128), V rows four rows per 16-lane block (ds_read_b64_tr_b16).
 template <int D>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
-  constexpr int K_ROWB = D * 2 + 16;
-  constexpr int K_BYTES = BN * K_ROWB;
-  constexpr int VT_BYTES = D * VT_ROWB;
-  constexpr int STAGE = K_BYTES + VT_BYTES;
-  constexpr int KS = D / 16;        // MFMA k-steps over head_dim
-  constexpr int MT = D / 32;        // O^T row tiles
-  constexpr int PCS = D / 8;        // 16-byte pieces per key row
-  constexpr int KEYS_PER_PASS = 256 / PCS;       // keys covered by one piece per thread
-  constexpr int K_PIECES = BN / KEYS_PER_PASS;   // pieces per thread for the K tile
-  // V: a thread owns a block of 4 consecutive keys x 8 head_dim elements; the tile has
-  // (BN / 4) * PCS such blocks: 256 for D = 128, 128 for D = 64 (then half the threads idle here)
-  constexpr int V_UNITS = 1;
-  static_assert((BN / 4) * PCS <= 256, "V tile has more 4x8 blocks than threads");
+__device__ __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+template <int D>
+__device__ __forceinline__ int swz_v(int r) {
+  return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : (((r & 1) << 2) | ((r >> 1) & 3));
+}
 
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// NCT = 32-column tiles per wave: 1 -> 8 waves (two per SIMD, the hardware overlaps one wave's
+// softmax with the other's MFMAs), 2 -> 4 waves with twice the register-level reuse of K/V
+// fragments.  Either way a workgroup owns 256 query columns.
+template <int D, int NCT>
+__global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
+  constexpr int NWAVES = 8 / NCT;
+  constexpr int WCOLS = 32 * NCT;              // query columns per wave
+  constexpr int ROWB = D * 2;                  // bytes per key row in LDS (no padding)
+  constexpr int TILE_BYTES = BN * ROWB;        // one K (or V) tile
+  constexpr int STAGE = 2 * TILE_BYTES;        // K tile followed by V tile
+  constexpr int KS = D / 16;                   // MFMA k-steps over head_dim
+  constexpr int MT = D / 32;                   // O^T row tiles
+  constexpr int PCS = D / 8;                   // 16-byte pieces per key row
+  constexpr int RPI = 64 / PCS;                // key rows covered by one wave-wide 16-byte load
+  constexpr int INSTS = BN / RPI / NWAVES;     // such loads per wave, tile and tensor
+  static_assert(INSTS >= 1, "tile too small for the wave count");
+
+  // two separate stage arrays: the compiler can then tell that the direct global->LDS loads
+  // into one stage do not alias the fragment reads of the other
+  __shared__ __align__(1024) unsigned char stage0[STAGE];
+  __shared__ __align__(1024) unsigned char stage1[STAGE];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
 
   // ---- work item ---------------------------------------------------------------------------
@@ -83,12 +113,12 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
   const int k_hi = min(k_lo + a.split_keys, kmax);
   const int n_kt = (k_hi - k_lo + BN - 1) / BN;
 
-  // ---- this lane's two query columns ---------------------------------------------------------
-  int pos[2], tokv[2], hq[2];
-  bool valid[2];
+  // ---- this lane's query columns ---------------------------------------------------------------
+  int pos[NCT], tokv[NCT], hq[NCT];
+  bool valid[NCT];
 #pragma unroll
-  for (int n = 0; n < 2; ++n) {
-    const int col = wave * 64 + n * 32 + l32;
+  for (int n = 0; n < NCT; ++n) {
+    const int col = wave * WCOLS + n * 32 + l32;
     const int tl = col & (a.TM - 1);
     const int t = tok0 + tl;
     valid[n] = t < a.n_sel;
@@ -96,209 +126,211 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     hq[n] = g * a.G + (col >> a.tm_shift);
     pos[n] = a.sel_idx[tokv[n]];
   }
-  int wmax = max(pos[0], pos[1]), wmin = min(pos[0], pos[1]);
+  int wmax = pos[0], wmin = pos[0];
+#pragma unroll
+  for (int n = 1; n < NCT; ++n) {
+    wmax = max(wmax, pos[n]);
+    wmin = min(wmin, pos[n]);
+  }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     wmax = max(wmax, __shfl_xor(wmax, off));
     wmin = min(wmin, __shfl_xor(wmin, off));
   }
+  wmax = __builtin_amdgcn_readfirstlane(wmax);
+  wmin = __builtin_amdgcn_readfirstlane(wmin);
 
   // Q^T fragments: B operand, lane = column, 8 consecutive head_dim elements per k-step
-  bf16x8 qf[2][KS];
+  bf16x8 qf[NCT][KS];
 #pragma unroll
-  for (int n = 0; n < 2; ++n) {
+  for (int n = 0; n < NCT; ++n) {
     const uint16_t* qp = a.q + ((size_t)tokv[n] * a.Hq + hq[n]) * D + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[n][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
-  // ---- staging maps --------------------------------------------------------------------------
-  const int pc_col = tid % PCS;          // 16-byte piece inside a key row
-  const int pc_key = tid / PCS;          // key inside a pass
+  // ---- global -> LDS staging (direct loads, no registers) ----------------------------------
+  // load i of this wave fills LDS rows (NWAVES * i + wave) * RPI .. + RPI - 1 of a tile; this
+  // lane supplies physical piece lane % PCS of row lane / PCS, i.e. logical piece
+  // (that ^ swizzle); NWAVES * RPI is a multiple of 16 rows, so the swizzle is the same for all i
+  const int ld_row = wave * RPI + lane / PCS;
+  const int ld_pk = (lane % PCS) ^ swz_k<D>(ld_row);
+  const int ld_pv = (lane % PCS) ^ swz_v<D>(ld_row);
   const size_t kv_row = (size_t)a.Hkv * D;
-  const uint16_t* kbase = a.k + (size_t)g * D + pc_col * 8;
-  const uint16_t* vbase = a.v + (size_t)g * D + pc_col * 8;
-  const bool v_active = pc_key < BN / 4;   // pc_key doubles as the 4-key group of the V block
-  u32x4 kr[K_PIECES];
-  u32x4 vr[V_UNITS][4];
-
-  auto load_tile = [&](int k0) {
+  const uint16_t* kbase = a.k + (size_t)g * D + ld_pk * 8;
+  const uint16_t* vbase = a.v + (size_t)g * D + ld_pv * 8;
+  auto issue_tile = [&](int k0, unsigned char* st) {
 #pragma unroll
-    for (int i = 0; i < K_PIECES; ++i) {
-      const int key = min(k0 + i * KEYS_PER_PASS + pc_key, a.n_ctx - 1);
-      kr[i] = *reinterpret_cast<const u32x4*>(kbase + key * kv_row);
-    }
-    if (v_active) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = min(k0 + pc_key * 4 + i, a.n_ctx - 1);
-        vr[0][i] = *reinterpret_cast<const u32x4*>(vbase + key * kv_row);
-      }
-    }
-  };
-  auto store_tile = [&](int buf) {
-    unsigned char* kb = smem + buf * STAGE;
-    unsigned char* vb = kb + K_BYTES;
-#pragma unroll
-    for (int i = 0; i < K_PIECES; ++i)
-      *reinterpret_cast<u32x4*>(kb + (i * KEYS_PER_PASS + pc_key) * K_ROWB + pc_col * 16) = kr[i];
-    if (v_active) {
-      constexpr int u = 0;
-      const int kg = pc_key;                              // group of 4 keys inside the tile, 0..15
-      const int sub = kg >> 3, kgl = kg & 7;
-      const int unit = sub * 4 + (kgl >> 2) * 2 + (kgl & 1);   // 16-byte unit (sub-tile, t, half)
-      const int inner = ((kgl >> 1) & 1) * 8;             // a = 0 / 1 inside the unit
-      const int sw = pc_col & 7;                          // (d >> 3) & 7 for all 8 rows of this thread
-      unsigned char* dst = vb + (pc_col * 8) * VT_ROWB + ((unit ^ sw) * 16) + inner;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        u32x2 lo, hi2;
-        lo[0] = __builtin_amdgcn_perm(vr[u][1][w], vr[u][0][w], 0x05040100u);
-        lo[1] = __builtin_amdgcn_perm(vr[u][3][w], vr[u][2][w], 0x05040100u);
-        hi2[0] = __builtin_amdgcn_perm(vr[u][1][w], vr[u][0][w], 0x07060302u);
-        hi2[1] = __builtin_amdgcn_perm(vr[u][3][w], vr[u][2][w], 0x07060302u);
-        *reinterpret_cast<u32x2*>(dst + (2 * w) * VT_ROWB) = lo;
-        *reinterpret_cast<u32x2*>(dst + (2 * w + 1) * VT_ROWB) = hi2;
-      }
+    for (int i = 0; i < INSTS; ++i) {
+      const int key = min(k0 + ld_row + NWAVES * RPI * i, a.n_ctx - 1);
+      const int slot = (NWAVES * i + wave) * 1024;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + key * kv_row),
+                                       (lds_ptr_t)(st + slot), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + key * kv_row),
+                                       (lds_ptr_t)(st + TILE_BYTES + slot), 16, 0, 0);
     }
   };
 
-  // ---- accumulators ---------------------------------------------------------------------------
-  f32x16 o[MT][2];
+  // ---- per-lane LDS read offsets ----------------------------------------------------------------
+  // K fragment (sub-tile u, k-step ks): row 32u + l32, logical piece 2ks + hi
+  int k_off[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = l32 * ROWB + (((2 * ks + hi) ^ swz_k<D>(l32)) * 16);
+  // V^T fragment (row tile m, sub-tile u, step t, half a2): 16-lane block b reads 4 key rows x
+  // 16 head_dim columns; lane j of the block addresses row j / 4, 8-byte chunk j % 4
+  const int vj = lane & 15, vdh = (lane >> 4) & 1;
+  int v_off[MT][2];
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[m][n][i] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY};
-  float l_run[2] = {0.f, 0.f};   // per-lane partial row sums; lanes l and l^32 are added at the end
-
-  const int k_frag = l32 * K_ROWB + hi * 16;
-  const int v_sw = l32 >> 3;            // (d >> 3) & 3 of this lane's row inside a 32-row tile
-
-  load_tile(k_lo);
-  store_tile(0);
-  __syncthreads();
-
-  for (int it = 0; it < n_kt; ++it) {
-    const int k0 = k_lo + it * BN;
-    const int buf = it & 1;
-    const bool more = it + 1 < n_kt;
-    if (more) load_tile(k0 + BN);
-
-    if (k0 <= wmax) {
-      const unsigned char* kb = smem + buf * STAGE;
-      const unsigned char* vb = kb + K_BYTES;
-
-      // ---- S^T = K Q^T for two 32-key sub-tiles x two 32-column tiles ------------------------
-      f32x16 s[2][2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int n = 0; n < 2; ++n)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[u][n][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 kf[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-          kf[u] = *reinterpret_cast<const bf16x8*>(kb + k_frag + u * 32 * K_ROWB + ks * 32);
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int n = 0; n < 2; ++n)
-            s[u][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[n][ks], s[u][n], 0, 0, 0);
-      }
-
-      // ---- causal mask (only tiles that reach past the earliest query of this wave) --------
-      if (k0 + BN - 1 > wmin) {
-#pragma unroll
-        for (int n = 0; n < 2; ++n) {
-          const int rel = pos[n] - k0 - 4 * hi;   // key offsets (32u + 8(i/4) + i%4) <= rel are visible
-#pragma unroll
-          for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              if (32 * u + 8 * (i >> 2) + (i & 3) > rel) s[u][n][i] = -INFINITY;
-        }
-      }
-
-      // ---- online softmax ----------------------------------------------------------------------
-      float alpha[2];
-      bool changed = false;
-#pragma unroll
-      for (int n = 0; n < 2; ++n) {
-        float mx = s[0][n][0];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[u][n][i]);
-        mx = fmaxf(mx, lane_xor32(mx));
-        const float m_new = fmaxf(m_run[n], mx * a.scale_log2);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        alpha[n] = __builtin_amdgcn_exp2f(m_run[n] - m_use);
-        changed |= m_new > m_run[n];
-        m_run[n] = m_new;
-        float rs = 0.f;
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][n][i], a.scale_log2, -m_use));
-            s[u][n][i] = p;
-            rs += p;
-          }
-        l_run[n] = l_run[n] * alpha[n] + rs;
-      }
-      if (__any(changed)) {
-#pragma unroll
-        for (int m = 0; m < MT; ++m)
-#pragma unroll
-          for (int n = 0; n < 2; ++n)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[m][n][i] *= alpha[n];
-      }
-
-      // ---- O^T += V^T P^T ------------------------------------------------------------------------
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          bf16x8 pf[2];
-#pragma unroll
-          for (int n = 0; n < 2; ++n) {
-            u32x4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = pack_bf16(s[u][n][8 * t + 2 * e], s[u][n][8 * t + 2 * e + 1]);
-            pf[n] = *reinterpret_cast<bf16x8*>(&w);
-          }
-          const int unit = u * 4 + t * 2 + hi;
-#pragma unroll
-          for (int m = 0; m < MT; ++m) {
-            const int sw = v_sw + 4 * (m & 1);
-            const bf16x8 vf =
-                *reinterpret_cast<const bf16x8*>(vb + (m * 32 + l32) * VT_ROWB + ((unit ^ sw) * 16));
-#pragma unroll
-            for (int n = 0; n < 2; ++n)
-              o[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[n], o[m][n], 0, 0, 0);
-          }
-        }
+    for (int a2 = 0; a2 < 2; ++a2) {
+      const int r = 8 * a2 + 4 * hi + (vj >> 2);        // + 32u + 16t, which leave the swizzle unchanged
+      const int pc = 4 * m + 2 * vdh + ((vj & 3) >> 1);
+      v_off[m][a2] = r * ROWB + ((pc ^ swz_v<D>(r)) * 16) + 8 * (vj & 1);
     }
 
-    if (more) store_tile(buf ^ 1);
-    __syncthreads();
+  // ---- accumulators ---------------------------------------------------------------------------
+  f32x16 o[MT][NCT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int n = 0; n < NCT; ++n)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[m][n][i] = 0.f;
+  float m_run[NCT], l_run[NCT];   // l: per-lane partial row sums; lanes l and l^32 are added at the end
+#pragma unroll
+  for (int n = 0; n < NCT; ++n) {
+    m_run[n] = -INFINITY;
+    l_run[n] = 0.f;
+  }
+
+  auto compute_tile = [&](const unsigned char* kb, int k0) {
+    const unsigned char* vb = kb + TILE_BYTES;
+    // ---- S^T = K Q^T for two 32-key sub-tiles ---------------------------------------------------
+    f32x16 s[2][NCT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int n = 0; n < NCT; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[u][n][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 kf[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) kf[u] = *reinterpret_cast<const bf16x8*>(kb + k_off[ks] + u * 32 * ROWB);
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int n = 0; n < NCT; ++n)
+          s[u][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[n][ks], s[u][n], 0, 0, 0);
+    }
+
+    // ---- causal mask (only tiles that reach past the earliest query of this wave) ----------
+    if (k0 + BN - 1 > wmin) {
+#pragma unroll
+      for (int n = 0; n < NCT; ++n) {
+        const int rel = pos[n] - k0 - 4 * hi;   // key offsets (32u + 8(i/4) + i%4) <= rel are visible
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (32 * u + 8 * (i >> 2) + (i & 3) > rel) s[u][n][i] = -INFINITY;
+      }
+    }
+
+    // ---- online softmax ------------------------------------------------------------------------
+    float alpha[NCT];
+    bool changed = false;
+#pragma unroll
+    for (int n = 0; n < NCT; ++n) {
+      float mx = s[0][n][0];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[u][n][i]);
+      mx = max_with_lane_xor32(mx);
+      const float m_new = fmaxf(m_run[n], mx * a.scale_log2);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      alpha[n] = __builtin_amdgcn_exp2f(m_run[n] - m_use);
+      changed |= m_new > m_run[n];
+      m_run[n] = m_new;
+      float rs = 0.f;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][n][i], a.scale_log2, -m_use));
+          s[u][n][i] = p;
+          rs += p;
+        }
+      l_run[n] = l_run[n] * alpha[n] + rs;
+    }
+    if (__any(changed)) {
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int n = 0; n < NCT; ++n)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[m][n][i] *= alpha[n];
+    }
+
+    // ---- O^T += V^T P^T --------------------------------------------------------------------------
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        bf16x8 pf[NCT];
+#pragma unroll
+        for (int n = 0; n < NCT; ++n) {
+          u32x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = pack_bf16(s[u][n][8 * t + 2 * e], s[u][n][8 * t + 2 * e + 1]);
+          pf[n] = *reinterpret_cast<bf16x8*>(&w);
+        }
+        const unsigned char* vrow = vb + (32 * u + 16 * t) * ROWB;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][0]));
+          const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][1]));
+          typedef __attribute__((ext_vector_type(8))) short s16x8;
+          const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(&both);
+#pragma unroll
+          for (int n = 0; n < NCT; ++n)
+            o[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[n], o[m][n], 0, 0, 0);
+        }
+      }
+  };
+
+  auto stage_ready = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's direct loads have landed
+    __syncthreads();                      // ... and everybody's; everybody is done with the old stage
+  };
+
+  issue_tile(k_lo, stage0);
+  stage_ready();
+  for (int it = 0; it < n_kt; it += 2) {
+    const int k0 = k_lo + it * BN;
+    if (it + 1 < n_kt) issue_tile(k0 + BN, stage1);
+    if (k0 <= wmax) compute_tile(stage0, k0);
+    stage_ready();
+    if (it + 1 >= n_kt) break;
+    if (it + 2 < n_kt) issue_tile(k0 + 2 * BN, stage0);
+    if (k0 + BN <= wmax) compute_tile(stage1, k0 + BN);
+    stage_ready();
   }
 
   // ---- epilogue -------------------------------------------------------------------------------
-  float l_tot[2];
+  float l_tot[NCT];
 #pragma unroll
-  for (int n = 0; n < 2; ++n) l_tot[n] = l_run[n] + lane_xor32(l_run[n]);
+  for (int n = 0; n < NCT; ++n) l_tot[n] = sum_with_lane_xor32(l_run[n]);
 
   if (a.n_splits == 1) {
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
+    for (int n = 0; n < NCT; ++n) {
       if (!valid[n]) continue;
       const float inv = 1.0f / l_tot[n];
       uint16_t* op = a.out + ((size_t)tokv[n] * a.Hq + hq[n]) * D + 4 * hi;
@@ -319,8 +351,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     const size_t item = ((size_t)tile * a.Hkv + g) * a.n_splits + split;
     float* base = a.partial + item * (size_t)(256 * (D + 2));
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int col = wave * 64 + n * 32 + l32;
+    for (int n = 0; n < NCT; ++n) {
+      const int col = wave * WCOLS + n * 32 + l32;
       float* op = base + (size_t)col * D + 4 * hi;
 #pragma unroll
       for (int m = 0; m < MT; ++m)
@@ -406,23 +438,30 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
   a.scale_log2 = scale * 1.4426950408889634f;
 
   const int D = cfg->head_dim;
-  const size_t shmem = 2 * (size_t)(BN * (D * 2 + 16) + D * VT_ROWB);
-  dim3 grid((unsigned)((size_t)p.n_tiles * cfg->n_kv_heads * p.n_splits)), block(256);
+  dim3 grid((unsigned)((size_t)p.n_tiles * cfg->n_kv_heads * p.n_splits));
   hipError_t e;
-  const void* fn = D == 128 ? reinterpret_cast<const void*>(attn_kernel<128>) : reinterpret_cast<const void*>(attn_kernel<64>);
-  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-  if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute (attention)");
+  static const int nct = []() {
+    const char* v = getenv("CT_ATTN_COLTILES");   // tuning knob: 32-column tiles per wave (1 or 2)
+    return (v != nullptr && v[0] == '2') ? 2 : 1;
+  }();
   int slot = prof_begin(KC_ATTN, s);
-  if (D == 128)
-    hipLaunchKernelGGL(attn_kernel<128>, grid, block, shmem, s, a);
-  else
-    hipLaunchKernelGGL(attn_kernel<64>, grid, block, shmem, s, a);
+  if (D == 128) {
+    if (nct == 1)
+      hipLaunchKernelGGL((attn_kernel<128, 1>), grid, dim3(512), 0, s, a);
+    else
+      hipLaunchKernelGGL((attn_kernel<128, 2>), grid, dim3(256), 0, s, a);
+  } else {
+    if (nct == 1)
+      hipLaunchKernelGGL((attn_kernel<64, 1>), grid, dim3(512), 0, s, a);
+    else
+      hipLaunchKernelGGL((attn_kernel<64, 2>), grid, dim3(256), 0, s, a);
+  }
   prof_end(KC_ATTN, slot, s);
   e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
   if (p.n_splits > 1) {
     const int64_t threads = (int64_t)n_sel * cfg->n_q_heads * (D / 4);
-    dim3 mgrid((unsigned)((threads + 255) / 256));
+    dim3 mgrid((unsigned)((threads + 255) / 256)), block(256);
     slot = prof_begin(KC_MERGE, s);
     if (D == 128)
       hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, block, 0, s, a);
