@@ -92,10 +92,13 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
   constexpr int INSTS = BN / RPI / NWAVES;     // such loads per wave, tile and tensor
   static_assert(INSTS >= 1, "tile too small for the wave count");
 
-  // two separate stage arrays: the compiler can then tell that the direct global->LDS loads
-  // into one stage do not alias the fragment reads of the other
+  // One array per pipeline stage (K tile followed by V tile): with separate arrays the
+  // compiler can tell that the direct global->LDS loads into one stage do not alias the
+  // fragment reads of another and does not serialise them.
   __shared__ __align__(1024) unsigned char stage0[STAGE];
   __shared__ __align__(1024) unsigned char stage1[STAGE];
+  __shared__ __align__(1024) unsigned char stage2[STAGE];
+  __shared__ __align__(1024) unsigned char stage3[STAGE];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
@@ -103,8 +106,10 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
   // ---- work item ---------------------------------------------------------------------------
   const int g = blockIdx.x % a.Hkv;
   const int rest = blockIdx.x / a.Hkv;
-  const int split = rest % a.n_splits;
-  const int tile = a.n_tiles - 1 - rest / a.n_splits;   // heaviest (latest) tiles first
+  // split-major order: the workgroups resident on an XCD at one time work on neighbouring
+  // tiles of the same key range and share its K/V lines in that XCD's L2
+  const int split = rest / a.n_tiles;
+  const int tile = a.n_tiles - 1 - rest % a.n_tiles;    // heaviest (latest) tiles first
   const int tok0 = tile * a.TM;
   const int last_tok = min(tok0 + a.TM, a.n_sel) - 1;
   const int kmax = a.sel_idx[last_tok] + 1;              // keys this tile can see
@@ -159,15 +164,21 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
   const size_t kv_row = (size_t)a.Hkv * D;
   const uint16_t* kbase = a.k + (size_t)g * D + ld_pk * 8;
   const uint16_t* vbase = a.v + (size_t)g * D + ld_pv * 8;
-  auto issue_tile = [&](int k0, unsigned char* st) {
+  // The loads are written as inline assembly (M0 = LDS base of the wave's 1 KiB slot, each lane
+  // lands at +16 * lane): the compiler then neither reorders them nor adds waits of its own, and
+  // the pipeline below orders them against the fragment reads with explicit vmcnt waits and
+  // workgroup barriers.
+  auto dma16 = [&](const uint16_t* src, unsigned char* dst) __attribute__((always_inline)) {
+    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(src) : "memory", "m0");
+  };
+  auto issue_tile = [&](int k0, unsigned char* st) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < INSTS; ++i) {
       const int key = min(k0 + ld_row + NWAVES * RPI * i, a.n_ctx - 1);
       const int slot = (NWAVES * i + wave) * 1024;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + key * kv_row),
-                                       (lds_ptr_t)(st + slot), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + key * kv_row),
-                                       (lds_ptr_t)(st + TILE_BYTES + slot), 16, 0, 0);
+      dma16(kbase + key * kv_row, st + slot);
+      dma16(vbase + key * kv_row, st + TILE_BYTES + slot);
     }
   };
 
@@ -204,7 +215,7 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
     l_run[n] = 0.f;
   }
 
-  auto compute_tile = [&](const unsigned char* kb, int k0) {
+  auto compute_tile = [&](const unsigned char* kb, int k0) __attribute__((always_inline)) {
     const unsigned char* vb = kb + TILE_BYTES;
     // ---- S^T = K Q^T for two 32-key sub-tiles ---------------------------------------------------
     f32x16 s[2][NCT];
@@ -305,23 +316,36 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
       }
   };
 
-  auto stage_ready = [&]() {
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's direct loads have landed
-    __syncthreads();                      // ... and everybody's; everybody is done with the old stage
+  // Four-stage pipeline: tiles i+1, i+2 are in flight and tile i+3 is issued while tile i is
+  // being consumed, so a miss in L2 has about three tile times to come back.  Loads past the
+  // last tile are still issued (row index clamped) to keep the outstanding-load count, and
+  // with it the wait below, the same in every iteration.
+  constexpr int LPT = 2 * INSTS;                                     // loads per wave and tile
+  constexpr int WAIT_2_TILES = ((2 * LPT) & 15) | (((2 * LPT) >> 4) << 14) | 0x0f70;   // s_waitcnt vmcnt(2 * LPT)
+  auto step = [&](int i, const unsigned char* cur, unsigned char* refill) __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(WAIT_2_TILES);   // this wave's loads of tile i have landed
+    __syncthreads();                            // everybody's have; everybody is done with tile i-1
+    issue_tile(k_lo + (i + 3) * BN, refill);    // into the stage tile i-1 was read from
+    const int k0 = k_lo + i * BN;
+    if (k0 <= wmax) compute_tile(cur, k0);
   };
-
+  // Every ordinary global load so far (indices, Q fragments) is waited for here, once: the
+  // compiler would otherwise guard their first use inside the loop with vmcnt waits that also
+  // wait for the look-ahead tile loads.
+  __builtin_amdgcn_s_waitcnt(0x0f70);
   issue_tile(k_lo, stage0);
-  stage_ready();
-  for (int it = 0; it < n_kt; it += 2) {
-    const int k0 = k_lo + it * BN;
-    if (it + 1 < n_kt) issue_tile(k0 + BN, stage1);
-    if (k0 <= wmax) compute_tile(stage0, k0);
-    stage_ready();
-    if (it + 1 >= n_kt) break;
-    if (it + 2 < n_kt) issue_tile(k0 + 2 * BN, stage0);
-    if (k0 + BN <= wmax) compute_tile(stage1, k0 + BN);
-    stage_ready();
+  issue_tile(k_lo + BN, stage1);
+  issue_tile(k_lo + 2 * BN, stage2);
+  for (int i = 0; i < n_kt; i += 4) {
+    step(i, stage0, stage3);
+    if (i + 1 >= n_kt) break;
+    step(i + 1, stage1, stage0);
+    if (i + 2 >= n_kt) break;
+    step(i + 2, stage2, stage1);
+    if (i + 3 >= n_kt) break;
+    step(i + 3, stage3, stage2);
   }
+  __builtin_amdgcn_s_waitcnt(0x0f70);           // drain the look-ahead loads before the LDS is released
 
   // ---- epilogue -------------------------------------------------------------------------------
   float l_tot[NCT];
