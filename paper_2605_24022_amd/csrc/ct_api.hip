@@ -4,6 +4,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -102,15 +103,21 @@ AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
   p.n_splits = 1;
   p.split_keys = n_ctx;
   p.ws_bytes = 0;
-  // Split the key range when (tile, kv head) pairs alone cannot fill 256 compute units a few
-  // times over; each split writes fp32 partial (O, m, l) to the workspace and a merge kernel
-  // combines them.
+  // Split the key range only when the (tile, kv head) pairs alone leave compute units idle:
+  // measured on MI355X, an unsplit launch wins as soon as there are about 1.5 pairs per
+  // compute unit (each split costs an fp32 partial (O, m, l) round trip and a merge kernel).
   const long pairs = (long)p.n_tiles * cfg->n_kv_heads;
-  if (pairs > 0 && pairs < 2048 && n_ctx > 2048) {
-    int want = (int)((2048 + pairs - 1) / pairs);       // splits needed for ~8 items per CU (half are empty: causal)
+  const long target = 384;                              // 1.5 x 256 compute units
+  if (pairs > 0 && pairs < target && n_ctx > 2048) {
+    int want = (int)((target + pairs - 1) / pairs);
     int keys = (n_ctx + want - 1) / want;
     keys = ((keys + 1023) / 1024) * 1024;               // whole K tiles, not too small
     if (keys < 2048) keys = 2048;
+    static const int forced = []() {                    // tuning knob: keys per split
+      const char* v = getenv("CT_ATTN_SPLIT_KEYS");
+      return v != nullptr ? atoi(v) : 0;
+    }();
+    if (forced >= 64) keys = (forced + 63) / 64 * 64;
     int ns = (n_ctx + keys - 1) / keys;
     if (ns > 1) {
       p.n_splits = ns;

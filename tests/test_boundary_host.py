@@ -135,10 +135,14 @@ def test_validate_indices():
     assert _status(B.ct_validate_indices, None, 4, 10) == B.CT_ERR_NULL
 
 
-def test_workspace_size_grows_with_problem():
+def test_workspace_size_covers_staging_and_partials():
     c = _cfg()
-    small = B.ct_workspace_bytes(c, 8192, 1228)
-    big = B.ct_workspace_bytes(c, 32768, 4915)
-    assert 0 < small < big
-    # q, k, v staging of the layer call must fit
-    assert big >= 4915 * (32 + 16) * 128 * 2
+    for n_ctx, n_sel in [(8192, 1228), (32768, 4915), (32768, 1638), (131072, 6553)]:
+        need = B.ct_workspace_bytes(c, n_ctx, n_sel)
+        # q, k, v staging of the layer call must fit
+        assert need >= n_sel * (32 + 16) * 128 * 2
+        assert need % 256 == 0
+    # few (tile, head) pairs -> the key range is split and fp32 partials need room as well
+    staging = 1638 * (32 + 16) * 128 * 2
+    assert B.ct_workspace_bytes(c, 32768, 1638) > staging + 26 * 8 * 2 * 256 * 128 * 4 - 1
+    assert B.ct_workspace_bytes(c, 0, 0) == 0 and B.ct_workspace_bytes(c, 100, 200) == 0
