@@ -80,6 +80,8 @@ def main() -> int:
     ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=96)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="run one plain 512 MiB device copy before the timed region (reference for HBM byte counters)")
     ap.add_argument("--no-profile-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
     args = ap.parse_args()
@@ -129,6 +131,13 @@ def main() -> int:
         B.ct_partial_prefill_layer(cfg, chunks, sp.n_chunks, hidden, rows, sel, sp.n_sel, ratio, wqkv, None,
                                    k_buf, v_buf, out, ws, ws_bytes, compute, copy)
 
+    if args.calibration_copy:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del src, dst
     log(f"warmup {args.warmup}, timing {args.steps} steps")
     for _ in range(args.warmup):
         step()
