@@ -25,6 +25,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per attention launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command
+# (scaled by a plain-copy calibration; see profiles/partial_prefill_layer_cfg3_r15.md).
+# Counters cannot be read live, so the figure is only attached to the workload it was
+# measured on.
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3-llama8b-32k-r15": (583.4 + 38.4) * 1024 * 1024}
 
 
 def log(msg: str) -> None:
@@ -178,7 +183,10 @@ def main() -> int:
         t_attn = (kern["attention"]["ms_per_step"] + kern.get("merge", {}).get("ms_per_step", 0.0)) * 1e-3
         ach = attn_flops / t_attn / 1e12
         roofline = {"bound": "mfma", "kernel": "selected attention (+ split merge)", "achieved": ach,
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get(sp.name),
+                    "traffic_unit": "bytes per launch (HBM fetch + write)",
+                    "algorithmic_flops_per_launch": attn_flops}
         extra["sel_attn_tflops"] = ach
     if "qkv" in kern:
         extra["qkv_tflops"] = qkv_flops / (kern["qkv"]["ms_per_step"] * 1e-3) / 1e12
