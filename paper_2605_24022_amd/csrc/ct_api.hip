@@ -258,6 +258,8 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
   if (n_sel == 0) return CT_OK;
   if (!q_sel || !k_buf || !v_buf || !sel_idx || !out)
     return fail(CT_ERR_NULL, "q_sel, k_buf, v_buf, sel_idx and out must be non-NULL");
+  if ((uint64_t)n_ctx * cfg->n_kv_heads * cfg->head_dim * 2 > 0xffffffffull)
+    return fail(CT_ERR_UNSUPPORTED, "K/V buffers beyond 4 GiB each (n_ctx %d) are not supported", n_ctx);
   AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
   if (p.ws_bytes > 0) {
     if (workspace == nullptr) return fail(CT_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", p.ws_bytes);
@@ -307,6 +309,8 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   const int32_t n_ctx = (int32_t)n_ctx64;
   tab.row_start[n_chunks] = n_ctx;
   if (n_sel > n_ctx) return fail(CT_ERR_SHAPE, "n_sel %d exceeds n_ctx %d", n_sel, n_ctx);
+  if ((uint64_t)n_ctx * cfg->n_kv_heads * cfg->head_dim * 2 > 0xffffffffull)
+    return fail(CT_ERR_UNSUPPORTED, "K/V buffers beyond 4 GiB each (n_ctx %d) are not supported", n_ctx);
   if (recompute_ratio >= 0.0) {
     if (!(recompute_ratio <= 1.0)) return fail(CT_ERR_RATIO, "recompute_ratio %g is above 1", recompute_ratio);
     int64_t want = (int64_t)floor(recompute_ratio * (double)n_ctx + 1e-9);

@@ -42,7 +42,7 @@ struct AttnArgs {
   uint16_t* out;
   float* lse;
   float* partial;     // workspace when n_splits > 1
-  int32_t n_sel, n_ctx, Hq, Hkv, G, TM, tm_shift;
+  int32_t n_sel, n_ctx, Hq, Hkv, G, TM, tm_shift, cols;
   int32_t n_tiles, n_splits, split_keys;
   float scale_log2;   // softmax scale * log2(e)
 };
@@ -75,33 +75,39 @@ __device__ __forceinline__ int swz_v(int r) {
   return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : (((r & 1) << 2) | ((r >> 1) & 3));
 }
 
-// NCT = 32-column tiles per wave: 1 -> 8 waves (two per SIMD, the hardware overlaps one wave's
-// softmax with the other's MFMAs), 2 -> 4 waves with twice the register-level reuse of K/V
-// fragments.  Either way a workgroup owns 256 query columns.
-template <int D, int NCT>
-__global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
-  constexpr int NWAVES = 8 / NCT;
-  constexpr int WCOLS = 32 * NCT;              // query columns per wave
+// A workgroup has 8 waves, two per SIMD; every wave owns 32 query columns (one MFMA column
+// tile) and all keys, so the workgroup owns 256 query columns.
+//
+// Ping-pong schedule.  The work of a wave on key tile i splits into a matrix-core part
+//   M(i): O^T += V^T(i-1) P^T(i-1), then S^T(i) = K(i) Q^T            (32 MFMAs)
+// and a vector-ALU part
+//   V(i): causal mask, online softmax of S^T(i) into P^T(i), rescale of O^T.
+// The loop runs in half periods separated by workgroup barriers.  Waves 0-3 (one per SIMD)
+// run M(i) in the even and V(i) in the odd half of period i; waves 4-7 run V(i-1) in the even
+// and M(i) in the odd half.  In every half period each SIMD therefore has one wave feeding
+// the matrix cores and one wave doing softmax arithmetic, and the barriers keep it that way.
+// K(i) and V(i-1) are the tiles in use during period i; K(i+2) and V(i+1) are fetched at its
+// start with direct global->LDS loads into three K and three V stages.
+template <int D>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel(AttnArgs a) {
+  constexpr int NWAVES = 8;
+  constexpr int COLS = 32 * NWAVES;            // query columns per workgroup
+  constexpr int NST = 3;                       // LDS stages per tensor
   constexpr int ROWB = D * 2;                  // bytes per key row in LDS (no padding)
   constexpr int TILE_BYTES = BN * ROWB;        // one K (or V) tile
-  constexpr int STAGE = 2 * TILE_BYTES;        // K tile followed by V tile
   constexpr int KS = D / 16;                   // MFMA k-steps over head_dim
   constexpr int MT = D / 32;                   // O^T row tiles
   constexpr int PCS = D / 8;                   // 16-byte pieces per key row
   constexpr int RPI = 64 / PCS;                // key rows covered by one wave-wide 16-byte load
   constexpr int INSTS = BN / RPI / NWAVES;     // such loads per wave, tile and tensor
-  static_assert(INSTS >= 1, "tile too small for the wave count");
+  static_assert(INSTS >= 1 && (NWAVES * RPI) % 16 == 0, "tile / wave count mismatch");
 
-  // One array per pipeline stage (K tile followed by V tile): with separate arrays the
-  // compiler can tell that the direct global->LDS loads into one stage do not alias the
-  // fragment reads of another and does not serialise them.
-  __shared__ __align__(1024) unsigned char stage0[STAGE];
-  __shared__ __align__(1024) unsigned char stage1[STAGE];
-  __shared__ __align__(1024) unsigned char stage2[STAGE];
-  __shared__ __align__(1024) unsigned char stage3[STAGE];
+  __shared__ __align__(1024) unsigned char k_lds[NST * TILE_BYTES];
+  __shared__ __align__(1024) unsigned char v_lds[NST * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
+  const bool group_b = wave >= NWAVES / 2;
 
   // ---- work item ---------------------------------------------------------------------------
   const int g = blockIdx.x % a.Hkv;
@@ -118,40 +124,24 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
   const int k_hi = min(k_lo + a.split_keys, kmax);
   const int n_kt = (k_hi - k_lo + BN - 1) / BN;
 
-  // ---- this lane's query columns ---------------------------------------------------------------
-  int pos[NCT], tokv[NCT], hq[NCT];
-  bool valid[NCT];
+  // ---- this lane's query column ------------------------------------------------------------------
+  const int col = wave * 32 + l32;
+  const int tok_raw = tok0 + (col & (a.TM - 1));
+  const bool valid = tok_raw < a.n_sel;
+  const int tokv = valid ? tok_raw : a.n_sel - 1;
+  const int hq = g * a.G + (col >> a.tm_shift);
+  const int pos = a.sel_idx[tokv];
+  int wmin = pos;
 #pragma unroll
-  for (int n = 0; n < NCT; ++n) {
-    const int col = wave * WCOLS + n * 32 + l32;
-    const int tl = col & (a.TM - 1);
-    const int t = tok0 + tl;
-    valid[n] = t < a.n_sel;
-    tokv[n] = valid[n] ? t : a.n_sel - 1;
-    hq[n] = g * a.G + (col >> a.tm_shift);
-    pos[n] = a.sel_idx[tokv[n]];
-  }
-  int wmax = pos[0], wmin = pos[0];
-#pragma unroll
-  for (int n = 1; n < NCT; ++n) {
-    wmax = max(wmax, pos[n]);
-    wmin = min(wmin, pos[n]);
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    wmax = max(wmax, __shfl_xor(wmax, off));
-    wmin = min(wmin, __shfl_xor(wmin, off));
-  }
-  wmax = __builtin_amdgcn_readfirstlane(wmax);
+  for (int off = 32; off >= 1; off >>= 1) wmin = min(wmin, __shfl_xor(wmin, off));
   wmin = __builtin_amdgcn_readfirstlane(wmin);
 
   // Q^T fragments: B operand, lane = column, 8 consecutive head_dim elements per k-step
-  bf16x8 qf[NCT][KS];
+  bf16x8 qf[KS];
+  {
+    const uint16_t* qp = a.q + ((size_t)tokv * a.Hq + hq) * D + hi * 8;
 #pragma unroll
-  for (int n = 0; n < NCT; ++n) {
-    const uint16_t* qp = a.q + ((size_t)tokv[n] * a.Hq + hq[n]) * D + hi * 8;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[n][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
   // ---- global -> LDS staging (direct loads, no registers) ----------------------------------
@@ -161,25 +151,29 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
   const int ld_row = wave * RPI + lane / PCS;
   const int ld_pk = (lane % PCS) ^ swz_k<D>(ld_row);
   const int ld_pv = (lane % PCS) ^ swz_v<D>(ld_row);
-  const size_t kv_row = (size_t)a.Hkv * D;
-  const uint16_t* kbase = a.k + (size_t)g * D + ld_pk * 8;
-  const uint16_t* vbase = a.v + (size_t)g * D + ld_pv * 8;
-  // The loads are written as inline assembly (M0 = LDS base of the wave's 1 KiB slot, each lane
-  // lands at +16 * lane): the compiler then neither reorders them nor adds waits of its own, and
-  // the pipeline below orders them against the fragment reads with explicit vmcnt waits and
-  // workgroup barriers.
-  auto dma16 = [&](const uint16_t* src, unsigned char* dst) __attribute__((always_inline)) {
-    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(src) : "memory", "m0");
+  // byte offsets from the tensor bases fit 32 bits (checked on the host)
+  const uint32_t kv_row_bytes = (uint32_t)a.Hkv * D * 2;
+  const uint32_t k_lane_off = ((uint32_t)g * D + ld_pk * 8) * 2;
+  const uint32_t v_lane_off = ((uint32_t)g * D + ld_pv * 8) * 2;
+  // The loads are inline assembly (M0 = LDS base of the wave's 1 KiB slot, each lane lands at
+  // +16 * lane): the compiler neither reorders them nor adds waits of its own; the pipeline
+  // below orders them against the fragment reads with explicit vmcnt waits and barriers.
+  auto dma16 = [&](const uint16_t* base, uint32_t byte_off, uint32_t lds_addr) __attribute__((always_inline)) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(base) : "memory", "m0");
   };
-  auto issue_tile = [&](int k0, unsigned char* st) __attribute__((always_inline)) {
+  const uint32_t k_lds_addr = (uint32_t)(uintptr_t)(lds_ptr_t)k_lds;
+  const uint32_t v_lds_addr = (uint32_t)(uintptr_t)(lds_ptr_t)v_lds;
+  // One wave-wide load: rows (NWAVES * idx + wave) * RPI .. of the tile that starts at key k0.
+  // Rows past the end of the context are clamped: they are masked, or belong to look-ahead
+  // tiles that are never consumed.
+  auto issue_one = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr, int idx) __attribute__((always_inline)) {
+    const int key = min(k0 + ld_row + NWAVES * RPI * idx, a.n_ctx - 1);
+    dma16(base, (uint32_t)key * kv_row_bytes + lane_off, stage_addr + (NWAVES * idx + wave) * 1024);
+  };
+  auto issue_rows = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < INSTS; ++i) {
-      const int key = min(k0 + ld_row + NWAVES * RPI * i, a.n_ctx - 1);
-      const int slot = (NWAVES * i + wave) * 1024;
-      dma16(kbase + key * kv_row, st + slot);
-      dma16(vbase + key * kv_row, st + TILE_BYTES + slot);
-    }
+    for (int i = 0; i < INSTS; ++i) issue_one(base, lane_off, k0, stage_addr, i);
   };
 
   // ---- per-lane LDS read offsets ----------------------------------------------------------------
@@ -200,195 +194,210 @@ __global__ __launch_bounds__(256 * 2 / NCT) void attn_kernel(AttnArgs a) {
       v_off[m][a2] = r * ROWB + ((pc ^ swz_v<D>(r)) * 16) + 8 * (vj & 1);
     }
 
-  // ---- accumulators ---------------------------------------------------------------------------
-  f32x16 o[MT][NCT];
+  // ---- state ---------------------------------------------------------------------------------------
+  f32x16 o[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
-    for (int n = 0; n < NCT; ++n)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[m][n][i] = 0.f;
-  float m_run[NCT], l_run[NCT];   // l: per-lane partial row sums; lanes l and l^32 are added at the end
-#pragma unroll
-  for (int n = 0; n < NCT; ++n) {
-    m_run[n] = -INFINITY;
-    l_run[n] = 0.f;
-  }
+    for (int i = 0; i < 16; ++i) o[m][i] = 0.f;
+  float m_run = -INFINITY;
+  float l_run = 0.f;   // per-lane partial row sum; lanes l and l^32 are added at the end
+  f32x16 s[2];         // S^T of the tile whose scores were computed last (two 32-key sub-tiles)
+  bf16x8 pf[2][2];     // P^T fragments (sub-tile u, 16-key step t) of the tile whose softmax was done last
 
-  auto compute_tile = [&](const unsigned char* kb, int k0) __attribute__((always_inline)) {
-    const unsigned char* vb = kb + TILE_BYTES;
-    // ---- S^T = K Q^T for two 32-key sub-tiles ---------------------------------------------------
-    f32x16 s[2][NCT];
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  auto load_vfrag = [&](const unsigned char* vrow, int m) __attribute__((always_inline)) -> bf16x8 {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][0]));
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][1]));
+    const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+    return *reinterpret_cast<const bf16x8*>(&both);
+  };
+
+  // ---- M part: O^T += V^T P^T (previous tile), S^T = K Q^T (this tile) ----------------------------
+  // The wave runs it at raised priority: its instruction stream is sparse (MFMAs, fragment
+  // reads, the look-ahead loads) and must not queue behind the dense softmax stream of the
+  // other wave on the SIMD.  The look-ahead loads are left to the softmax wave.
+  auto part_m = [&](bool do_pv, const unsigned char* vb, bool do_qk, const unsigned char* kb) __attribute__((always_inline)) {
+    __builtin_amdgcn_s_setprio(3);
+    if (do_pv) {
+      bf16x8 vf[2][MT];
+#pragma unroll
+      for (int m = 0; m < MT; ++m) vf[0][m] = load_vfrag(vb, m);
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi) {      // group gi = (sub-tile u, step t)
+        if (gi + 1 < 4) {
+#pragma unroll
+          for (int m = 0; m < MT; ++m) vf[(gi + 1) & 1][m] = load_vfrag(vb + 16 * (gi + 1) * ROWB, m);
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+          o[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[gi & 1][m], pf[gi >> 1][gi & 1], o[m], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);   // keep the fragment look-ahead at one group (register budget)
+      }
+    }
+    if (do_qk) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
+      bf16x8 kf[2][2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) kf[0][u] = *reinterpret_cast<const bf16x8*>(kb + k_off[0] + u * 32 * ROWB);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) {
+#pragma unroll
+          for (int u = 0; u < 2; ++u)
+            kf[(ks + 1) & 1][u] = *reinterpret_cast<const bf16x8*>(kb + k_off[ks + 1] + u * 32 * ROWB);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][u], qf[ks], s[u], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+
+  // ---- V part: causal mask, online softmax, P^T fragments, rescale of O^T -------------------------
+  auto part_v = [&](int k0) __attribute__((always_inline)) {
+    if (k0 + BN - 1 > wmin) {   // only tiles that reach past the earliest query of this wave
+      const int rel = pos - k0 - 4 * hi;   // key offsets (32u + 8(i/4) + i%4) <= rel are visible
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (32 * u + 8 * (i >> 2) + (i & 3) > rel) s[u][i] = -INFINITY;
+    }
+    float mx = s[0][0];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int n = 0; n < NCT; ++n)
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[u][i]);
+    mx = max_with_lane_xor32(mx);
+    const float m_new = fmaxf(m_run, mx * a.scale_log2);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    const bool changed = m_new > m_run;
+    m_run = m_new;
+    float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[u][n][i] = 0.f;
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 kf[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) kf[u] = *reinterpret_cast<const bf16x8*>(kb + k_off[ks] + u * 32 * ROWB);
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int n = 0; n < NCT; ++n)
-          s[u][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u], qf[n][ks], s[u][n], 0, 0, 0);
-    }
-
-    // ---- causal mask (only tiles that reach past the earliest query of this wave) ----------
-    if (k0 + BN - 1 > wmin) {
-#pragma unroll
-      for (int n = 0; n < NCT; ++n) {
-        const int rel = pos[n] - k0 - 4 * hi;   // key offsets (32u + 8(i/4) + i%4) <= rel are visible
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (32 * u + 8 * (i >> 2) + (i & 3) > rel) s[u][n][i] = -INFINITY;
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][i], a.scale_log2, -m_use));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][i + 1], a.scale_log2, -m_use));
+        s[u][i] = p0;
+        s[u][i + 1] = p1;
+        rs0 += p0;
+        rs1 += p1;
       }
-    }
-
-    // ---- online softmax ------------------------------------------------------------------------
-    float alpha[NCT];
-    bool changed = false;
-#pragma unroll
-    for (int n = 0; n < NCT; ++n) {
-      float mx = s[0][n][0];
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[u][n][i]);
-      mx = max_with_lane_xor32(mx);
-      const float m_new = fmaxf(m_run[n], mx * a.scale_log2);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      alpha[n] = __builtin_amdgcn_exp2f(m_run[n] - m_use);
-      changed |= m_new > m_run[n];
-      m_run[n] = m_new;
-      float rs = 0.f;
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][n][i], a.scale_log2, -m_use));
-          s[u][n][i] = p;
-          rs += p;
-        }
-      l_run[n] = l_run[n] * alpha[n] + rs;
-    }
-    if (__any(changed)) {
-#pragma unroll
-      for (int m = 0; m < MT; ++m)
-#pragma unroll
-        for (int n = 0; n < NCT; ++n)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[m][n][i] *= alpha[n];
-    }
-
-    // ---- O^T += V^T P^T --------------------------------------------------------------------------
+    l_run = l_run * alpha + (rs0 + rs1);
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        bf16x8 pf[NCT];
+        u32x4 w;
 #pragma unroll
-        for (int n = 0; n < NCT; ++n) {
-          u32x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = pack_bf16(s[u][n][8 * t + 2 * e], s[u][n][8 * t + 2 * e + 1]);
-          pf[n] = *reinterpret_cast<bf16x8*>(&w);
-        }
-        const unsigned char* vrow = vb + (32 * u + 16 * t) * ROWB;
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][0]));
-          const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][1]));
-          typedef __attribute__((ext_vector_type(8))) short s16x8;
-          const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(&both);
-#pragma unroll
-          for (int n = 0; n < NCT; ++n)
-            o[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[n], o[m][n], 0, 0, 0);
-        }
+        for (int e = 0; e < 4; ++e) w[e] = pack_bf16(s[u][8 * t + 2 * e], s[u][8 * t + 2 * e + 1]);
+        pf[u][t] = *reinterpret_cast<bf16x8*>(&w);
       }
+    if (__any(changed)) {
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[m][i] *= alpha;
+    }
   };
 
-  // Four-stage pipeline: tiles i+1, i+2 are in flight and tile i+3 is issued while tile i is
-  // being consumed, so a miss in L2 has about three tile times to come back.  Loads past the
-  // last tile are still issued (row index clamped) to keep the outstanding-load count, and
-  // with it the wait below, the same in every iteration.
-  constexpr int LPT = 2 * INSTS;                                     // loads per wave and tile
-  constexpr int WAIT_2_TILES = ((2 * LPT) & 15) | (((2 * LPT) >> 4) << 14) | 0x0f70;   // s_waitcnt vmcnt(2 * LPT)
-  auto step = [&](int i, const unsigned char* cur, unsigned char* refill) __attribute__((always_inline)) {
-    __builtin_amdgcn_s_waitcnt(WAIT_2_TILES);   // this wave's loads of tile i have landed
-    __syncthreads();                            // everybody's have; everybody is done with tile i-1
-    issue_tile(k_lo + (i + 3) * BN, refill);    // into the stage tile i-1 was read from
-    const int k0 = k_lo + i * BN;
-    if (k0 <= wmax) compute_tile(cur, k0);
-  };
+  // ---- the half-period loop ------------------------------------------------------------------------
+  // Loads past the last tile are still issued (row index clamped) so that the number of loads
+  // outstanding at the wait, and with it the wait itself, is the same in every period.
+  constexpr int LPP = 2 * INSTS;                                              // loads per wave and period
+  constexpr int WAIT_OLDER = (LPP & 15) | ((LPP >> 4) << 14) | 0x0f70;        // s_waitcnt vmcnt(LPP)
   // Every ordinary global load so far (indices, Q fragments) is waited for here, once: the
   // compiler would otherwise guard their first use inside the loop with vmcnt waits that also
   // wait for the look-ahead tile loads.
   __builtin_amdgcn_s_waitcnt(0x0f70);
-  issue_tile(k_lo, stage0);
-  issue_tile(k_lo + BN, stage1);
-  issue_tile(k_lo + 2 * BN, stage2);
-  for (int i = 0; i < n_kt; i += 4) {
-    step(i, stage0, stage3);
-    if (i + 1 >= n_kt) break;
-    step(i + 1, stage1, stage0);
-    if (i + 2 >= n_kt) break;
-    step(i + 2, stage2, stage1);
-    if (i + 3 >= n_kt) break;
-    step(i + 3, stage3, stage2);
+  issue_rows(a.k, k_lane_off, k_lo, k_lds_addr);                           // K(0)
+  issue_rows(a.v, v_lane_off, k_lo, v_lds_addr + 2 * TILE_BYTES);          // stands in for V(-1): keeps the load count uniform
+  issue_rows(a.k, k_lane_off, k_lo + BN, k_lds_addr + TILE_BYTES);         // K(1)
+  issue_rows(a.v, v_lane_off, k_lo, v_lds_addr);                           // V(0)
+  __builtin_amdgcn_s_waitcnt(WAIT_OLDER);                                  // K(0) has landed (and the stand-in)
+  __syncthreads();
+  auto end_of_period = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(WAIT_OLDER);     // this wave's loads of the previous period have landed
+    __syncthreads();                            // everybody's have; everybody is done with K(i), V(i-1)
+  };
+  // Period i uses K(i) and V(i-1); its M parts fetch K(i+2) and V(i+1) into the stages of
+  // K(i-1) and V(i-2), which nobody reads any more.  The two groups run separate loops with
+  // the same number of barriers.
+  // The look-ahead loads of period i (K(i+2), V(i+1)) are issued by each wave right before its
+  // softmax part: that wave has time to spare, and the wave in the MFMA part is not held up by
+  // the texture addresser.
+  auto refill = [&](int i, int st_im1, int st_ip1) __attribute__((always_inline)) {
+    issue_rows(a.k, k_lane_off, k_lo + (i + 2) * BN, k_lds_addr + st_im1 * TILE_BYTES);
+    issue_rows(a.v, v_lane_off, k_lo + (i + 1) * BN, v_lds_addr + st_ip1 * TILE_BYTES);
+  };
+  int st_i = 0, st_im1 = 2;                     // stage indices of tiles i and i - 1 (i mod 3)
+  if (!group_b) {
+    for (int i = 0; i <= n_kt; ++i) {
+      const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
+      part_m(i >= 1, v_lds + st_im1 * TILE_BYTES, i < n_kt, k_lds + st_i * TILE_BYTES);
+      __syncthreads();
+      refill(i, st_im1, st_ip1);
+      if (i < n_kt) part_v(k_lo + i * BN);
+      end_of_period();
+      st_im1 = st_i;
+      st_i = st_ip1;
+    }
+  } else {
+    for (int i = 0; i <= n_kt; ++i) {
+      const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
+      refill(i, st_im1, st_ip1);
+      if (i >= 1) part_v(k_lo + (i - 1) * BN);
+      __syncthreads();
+      part_m(i >= 1, v_lds + st_im1 * TILE_BYTES, i < n_kt, k_lds + st_i * TILE_BYTES);
+      end_of_period();
+      st_im1 = st_i;
+      st_i = st_ip1;
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);           // drain the look-ahead loads before the LDS is released
 
   // ---- epilogue -------------------------------------------------------------------------------
-  float l_tot[NCT];
-#pragma unroll
-  for (int n = 0; n < NCT; ++n) l_tot[n] = sum_with_lane_xor32(l_run[n]);
-
+  const float l_tot = sum_with_lane_xor32(l_run);
   if (a.n_splits == 1) {
-#pragma unroll
-    for (int n = 0; n < NCT; ++n) {
-      if (!valid[n]) continue;
-      const float inv = 1.0f / l_tot[n];
-      uint16_t* op = a.out + ((size_t)tokv[n] * a.Hq + hq[n]) * D + 4 * hi;
+    if (valid) {
+      const float inv = 1.0f / l_tot;
+      uint16_t* op = a.out + ((size_t)tokv * a.Hq + hq) * D + 4 * hi;
 #pragma unroll
       for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           u32x2 w;
-          w[0] = pack_bf16(o[m][n][4 * q4 + 0] * inv, o[m][n][4 * q4 + 1] * inv);
-          w[1] = pack_bf16(o[m][n][4 * q4 + 2] * inv, o[m][n][4 * q4 + 3] * inv);
+          w[0] = pack_bf16(o[m][4 * q4 + 0] * inv, o[m][4 * q4 + 1] * inv);
+          w[1] = pack_bf16(o[m][4 * q4 + 2] * inv, o[m][4 * q4 + 3] * inv);
           *reinterpret_cast<u32x2*>(op + m * 32 + 8 * q4) = w;
         }
       if (a.lse != nullptr && hi == 0)
-        a.lse[(size_t)tokv[n] * a.Hq + hq[n]] = (m_run[n] + __builtin_log2f(l_tot[n])) * 0.69314718055994531f;
+        a.lse[(size_t)tokv * a.Hq + hq] = (m_run + __builtin_log2f(l_tot)) * 0.69314718055994531f;
     }
   } else {
-    // partial results: [item][256 columns][D] fp32, then m[256], l[256]
+    // partial results: [item][COLS columns][D] fp32, then m[COLS], l[COLS]
     const size_t item = ((size_t)tile * a.Hkv + g) * a.n_splits + split;
-    float* base = a.partial + item * (size_t)(256 * (D + 2));
+    float* base = a.partial + item * (size_t)(COLS * (D + 2));
+    float* op = base + (size_t)col * D + 4 * hi;
 #pragma unroll
-    for (int n = 0; n < NCT; ++n) {
-      const int col = wave * WCOLS + n * 32 + l32;
-      float* op = base + (size_t)col * D + 4 * hi;
+    for (int m = 0; m < MT; ++m)
 #pragma unroll
-      for (int m = 0; m < MT; ++m)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 w = {o[m][n][4 * q4 + 0], o[m][n][4 * q4 + 1], o[m][n][4 * q4 + 2], o[m][n][4 * q4 + 3]};
-          *reinterpret_cast<f32x4*>(op + m * 32 + 8 * q4) = w;
-        }
-      if (hi == 0) {
-        base[256 * D + col] = m_run[n];
-        base[256 * D + 256 + col] = l_tot[n];
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 w = {o[m][4 * q4 + 0], o[m][4 * q4 + 1], o[m][4 * q4 + 2], o[m][4 * q4 + 3]};
+        *reinterpret_cast<f32x4*>(op + m * 32 + 8 * q4) = w;
       }
+    if (hi == 0) {
+      base[COLS * D + col] = m_run;
+      base[COLS * D + COLS + col] = l_tot;
     }
   }
 }
@@ -410,16 +419,17 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
   const int kmax = a.sel_idx[last_tok] + 1;
   const int ns = min(a.n_splits, (kmax + a.split_keys - 1) / a.split_keys);
   const size_t item0 = ((size_t)tile * a.Hkv + g) * a.n_splits;
-  const size_t istride = (size_t)(256 * (D + 2));
+  const int C = a.cols;
+  const size_t istride = (size_t)C * (D + 2);
   float mx = -INFINITY;
-  for (int i = 0; i < ns; ++i) mx = fmaxf(mx, a.partial[(item0 + i) * istride + 256 * D + col]);
+  for (int i = 0; i < ns; ++i) mx = fmaxf(mx, a.partial[(item0 + i) * istride + (size_t)C * D + col]);
   float L = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int i = 0; i < ns; ++i) {
     const float* base = a.partial + (item0 + i) * istride;
-    const float mi = base[256 * D + col];
+    const float mi = base[(size_t)C * D + col];
     const float w = __builtin_amdgcn_exp2f(mi - mx);     // 0 for a split with nothing visible (m = -inf)
-    L += w * base[256 * D + 256 + col];
+    L += w * base[(size_t)C * D + C + col];
     const f32x4 oi = *reinterpret_cast<const f32x4*>(base + (size_t)col * D + d4);
     if (w > 0.f) acc += w * oi;
   }
@@ -453,6 +463,7 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
   a.Hkv = cfg->n_kv_heads;
   a.G = cfg->n_q_heads / cfg->n_kv_heads;
   a.TM = p.tile_tokens;
+  a.cols = 256;
   a.tm_shift = 0;
   while ((1 << a.tm_shift) < a.TM) ++a.tm_shift;
   a.n_tiles = p.n_tiles;
@@ -464,22 +475,11 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
   const int D = cfg->head_dim;
   dim3 grid((unsigned)((size_t)p.n_tiles * cfg->n_kv_heads * p.n_splits));
   hipError_t e;
-  static const int nct = []() {
-    const char* v = getenv("CT_ATTN_COLTILES");   // tuning knob: 32-column tiles per wave (1 or 2)
-    return (v != nullptr && v[0] == '2') ? 2 : 1;
-  }();
   int slot = prof_begin(KC_ATTN, s);
-  if (D == 128) {
-    if (nct == 1)
-      hipLaunchKernelGGL((attn_kernel<128, 1>), grid, dim3(512), 0, s, a);
-    else
-      hipLaunchKernelGGL((attn_kernel<128, 2>), grid, dim3(256), 0, s, a);
-  } else {
-    if (nct == 1)
-      hipLaunchKernelGGL((attn_kernel<64, 1>), grid, dim3(512), 0, s, a);
-    else
-      hipLaunchKernelGGL((attn_kernel<64, 2>), grid, dim3(256), 0, s, a);
-  }
+  if (D == 128)
+    hipLaunchKernelGGL(attn_kernel<128>, grid, dim3(512), 0, s, a);
+  else
+    hipLaunchKernelGGL(attn_kernel<64>, grid, dim3(512), 0, s, a);
   prof_end(KC_ATTN, slot, s);
   e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
