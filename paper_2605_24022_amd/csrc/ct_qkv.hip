@@ -7,14 +7,17 @@
 //   - both elements of every RoPE pair of a token sit in the same lane (no cross-lane
 //     traffic in the epilogue), and the token's position is a per-lane scalar;
 //   - results leave as 8-byte stores of four consecutive bf16 features.
-// Both operands are K-contiguous in memory (W is out-features major, X is token major), so
-// they are staged through LDS with plain 128-bit copies and read back as MFMA fragments
-// with 128-bit LDS reads; rows are padded by 16 bytes to spread the banks.
+// Both operands are K-contiguous in memory (W is out-features major, X is token major).
+// Tiles go from global memory straight into LDS (global_load_lds_dwordx4, no register
+// staging): a wave-wide load fills 8 rows of 128 bytes, the 16-byte pieces of a row are
+// XOR-swizzled so that the 128-bit fragment reads of 16 consecutive rows hit distinct banks.
 //
-// Workgroup: 256 threads = 4 waves (2 x 2), tile 256 features x 128 tokens x 64 (K step),
-// wave tile 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16, double-buffered LDS.
+// Workgroup: 512 threads = 8 waves (2 feature halves x 4 token quarters), tile 256 features x
+// 256 tokens x 64 (K step), wave tile 128 x 64 = 4 x 2 MFMA tiles of
+// v_mfma_f32_32x32x16_bf16, two LDS stages of 64 KiB, one barrier per K step.  Two waves
+// share a SIMD, so one wave's fragment reads and waits hide behind the other's MFMAs.
 // Workgroups are numbered so that the ones resident on one XCD (ids congruent mod 8) cover a
-// 4 x 8 patch of tiles and share their W and X tiles in that XCD's L2.
+// patch of neighbouring tiles and share their W and X tiles in that XCD's L2.
 #include "ct_internal.h"
 
 namespace ct {
@@ -22,14 +25,15 @@ namespace ct {
 namespace {
 
 constexpr int BF = 256;           // features per workgroup
-constexpr int BT = 128;           // tokens per workgroup
+constexpr int BT = 256;           // tokens per workgroup
 constexpr int BK = 64;            // reduction elements per stage
-constexpr int ROWB = BK * 2 + 16; // padded LDS row in bytes
+constexpr int ROWB = BK * 2;      // LDS row in bytes (unpadded, swizzled)
 constexpr int A_BYTES = BF * ROWB;
 constexpr int B_BYTES = BT * ROWB;
 constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-constexpr int A_PIECES = BF * BK / 8 / 256;  // 16-byte pieces per thread and stage
-constexpr int B_PIECES = BT * BK / 8 / 256;
+constexpr int NWAVES = 8;
+constexpr int A_LOADS = BF / 8 / NWAVES;   // wave-wide loads (8 rows each) per wave and stage
+constexpr int B_LOADS = BT / 8 / NWAVES;
 
 struct QkvArgs {
   const uint16_t* hidden;
@@ -51,10 +55,15 @@ __device__ __forceinline__ int32_t position_of_row(const ChunkTable& tab, int32_
   return tab.new_start[c] + (r - tab.row_start[c]);
 }
 
+// swizzle of the 16-byte pieces of LDS row r (rows are 128 bytes: two rows per 256-byte bank span)
+__device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
+
 template <int D, int STYLE>
-__global__ __launch_bounds__(256) void qkv_kernel(QkvArgs a, RopeTable rope, ChunkTable chunks) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void qkv_kernel(QkvArgs a, RopeTable rope,
+                                                                                            ChunkTable chunks) {
+  __shared__ __align__(1024) unsigned char lds[2 * STAGE_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
 
   // ---- workgroup -> tile, XCD aware (consecutive ids go to different XCDs) ----------------
@@ -72,30 +81,49 @@ __global__ __launch_bounds__(256) void qkv_kernel(QkvArgs a, RopeTable rope, Chu
   const int f_blk = (fp * PF + r2 % fw) * BF;
   const int t_blk = (tp * PT + r2 / fw) * BT;
 
-  // ---- global -> LDS staging pointers -------------------------------------------------------
-  const uint16_t* ga[A_PIECES];
-  const uint16_t* gb[B_PIECES];
-  int la[A_PIECES], lb[B_PIECES];
+  // ---- global -> LDS loads -------------------------------------------------------------------
+  // load j of this wave fills LDS rows (NWAVES * j + wave) * 8 .. + 7 of the A (or B) tile; this
+  // lane supplies physical piece lane % 8 of row lane / 8, i.e. logical piece (that ^ swizzle).
+  // Byte offsets from the tensor bases fit 32 bits (checked on the host); the K step advances
+  // the scalar base, so the per-lane offsets are loop invariant.
+  uint32_t a_off[A_LOADS], b_off[B_LOADS];
 #pragma unroll
-  for (int i = 0; i < A_PIECES; ++i) {
-    const int p = i * 256 + tid, row = p >> 3, col = p & 7;
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int row = (NWAVES * j + wave) * 8 + (lane >> 3);
     const int f = min(f_blk + row, a.O - 1);
-    ga[i] = a.wqkv + (size_t)f * a.E + col * 8;
-    la[i] = row * ROWB + col * 16;
+    a_off[j] = ((uint32_t)f * a.E + (((lane & 7) ^ swz(row)) * 8)) * 2;
   }
 #pragma unroll
-  for (int i = 0; i < B_PIECES; ++i) {
-    const int p = i * 256 + tid, row = p >> 3, col = p & 7;
+  for (int j = 0; j < B_LOADS; ++j) {
+    const int row = (NWAVES * j + wave) * 8 + (lane >> 3);
     const int t = min(t_blk + row, a.n_sel - 1);
-    const int64_t xr = a.hidden_rows ? (int64_t)a.hidden_rows[t] : (int64_t)t;
-    gb[i] = a.hidden + xr * a.E + col * 8;
-    lb[i] = A_BYTES + row * ROWB + col * 16;
+    const uint32_t xr = a.hidden_rows ? (uint32_t)a.hidden_rows[t] : (uint32_t)t;
+    b_off[j] = (xr * a.E + (((lane & 7) ^ swz(row)) * 8)) * 2;
   }
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  const uint32_t lds_addr0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  auto dma16 = [&](const uint16_t* base, uint32_t byte_off, uint32_t lds_addr) __attribute__((always_inline)) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(base) : "memory");
+  };
+  auto issue_stage = [&](int k0, int stage) __attribute__((always_inline)) {
+    const uint16_t* wk = a.wqkv + k0;      // scalar bases advanced to the K step
+    const uint16_t* xk = a.hidden + k0;
+    const uint32_t st = lds_addr0 + stage * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) dma16(wk, a_off[j], st + (NWAVES * j + wave) * 1024);
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) dma16(xk, b_off[j], st + A_BYTES + (NWAVES * j + wave) * 1024);
+  };
 
-  const int wf = wave >> 1, wt = wave & 1;
-  // fragment read offsets inside a stage (bytes)
-  const int a_frag = (wf * 128 + l32) * ROWB + hi * 16;
-  const int b_frag = A_BYTES + (wt * 64 + l32) * ROWB + hi * 16;
+  const int wf = wave & 1, wt = wave >> 1;
+  // fragment read offsets inside a stage (bytes): row base + swizzled piece, per k-step
+  int a_frag[BK / 16], b_frag[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) {
+    a_frag[ks] = (wf * 128 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+    b_frag[ks] = A_BYTES + (wt * 64 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+  }
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -105,46 +133,28 @@ __global__ __launch_bounds__(256) void qkv_kernel(QkvArgs a, RopeTable rope, Chu
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
 
-  u32x4 ra[A_PIECES], rb[B_PIECES];
-  auto load_stage = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < A_PIECES; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + k0);
-#pragma unroll
-    for (int i = 0; i < B_PIECES; ++i) rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + k0);
-  };
-  auto store_stage = [&](int buf) {
-    unsigned char* base = smem + buf * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < A_PIECES; ++i) *reinterpret_cast<u32x4*>(base + la[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_PIECES; ++i) *reinterpret_cast<u32x4*>(base + lb[i]) = rb[i];
-  };
-
   const int nk = a.E / BK;
-  load_stage(0);
-  store_stage(0);
-  __syncthreads();
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // ordinary loads so far (row indices) are complete
+  issue_stage(0, 0);
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) load_stage((kt + 1) * BK);
-    const unsigned char* base = smem + buf * STAGE_BYTES;
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's part of stage kt has landed
+    __syncthreads();                      // everybody's has; everybody is done reading the other stage
+    if (kt + 1 < nk) issue_stage((kt + 1) * BK, buf ^ 1);
+    const unsigned char* base = lds + buf * STAGE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 fa[4], fb[2];
 #pragma unroll
-      for (int m = 0; m < 4; ++m)
-        fa[m] = *reinterpret_cast<const bf16x8*>(base + a_frag + m * 32 * ROWB + ks * 32);
+      for (int m = 0; m < 4; ++m) fa[m] = *reinterpret_cast<const bf16x8*>(base + a_frag[ks] + m * 32 * ROWB);
 #pragma unroll
-      for (int n = 0; n < 2; ++n)
-        fb[n] = *reinterpret_cast<const bf16x8*>(base + b_frag + n * 32 * ROWB + ks * 32);
+      for (int n = 0; n < 2; ++n) fb[n] = *reinterpret_cast<const bf16x8*>(base + b_frag[ks] + n * 32 * ROWB);
 #pragma unroll
       for (int m = 0; m < 4; ++m)
 #pragma unroll
         for (int n = 0; n < 2; ++n)
           acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_stage(buf ^ 1);
-    __syncthreads();
   }
 
   // ---- epilogue: bias, RoPE, round, store ---------------------------------------------------
@@ -263,14 +273,10 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
   }
   const int total = a.nF * a.nT;
   const int per_xcd = (total + 7) / 8;
-  dim3 grid(per_xcd * 8), block(256);
-  const size_t shmem = 2 * STAGE_BYTES;
+  dim3 grid(per_xcd * 8), block(512);
   auto launch = [&](auto kernel) -> hipError_t {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)shmem);
-    if (e != hipSuccess) return e;
     int slot = prof_begin(KC_QKV, s);
-    hipLaunchKernelGGL(kernel, grid, block, shmem, s, a, rope, tab);
+    hipLaunchKernelGGL(kernel, grid, block, 0, s, a, rope, tab);
     prof_end(KC_QKV, slot, s);
     return hipGetLastError();
   };
