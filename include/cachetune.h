@@ -12,7 +12,8 @@
  *     "host" pointers are ordinary process memory, "pinned host" is hipHostMalloc memory.
  *   - KV layout is token-major [tokens, n_kv_heads, head_dim] (the paper's N x H x D).
  *   - The caller owns every buffer and both streams.  The library allocates nothing and
- *     keeps no state besides a thread-local error string.  `stream` arguments are
+ *     keeps no state besides a thread-local error string, the opt-in profiling events and a
+ *     pool of HIP events the stack call reuses.  `stream` arguments are
  *     hipStream_t values passed as void* (NULL = the default stream).
  *   - Calls only enqueue work: no entry point synchronises the device or the host with it.
  *     Results are valid once the stream has passed the call's last kernel.
@@ -79,7 +80,7 @@ typedef struct {
  * positions).  For s in [0, n_sel): x = hidden[hidden_rows ? hidden_rows[s] : s, :],
  * [q|k|v] = x * wqkv^T (+ bias), RoPE on every q and k head at position sel_pos[s],
  * results rounded to bf16 (nearest even) from fp32 accumulators.
- *   hidden      device bf16 [*, hidden]
+ *   hidden      device bf16 [*, hidden]; rows read must lie within 4 GiB of the base
  *   hidden_rows device int32 [n_sel] or NULL (hidden is already compact)
  *   sel_pos     device int32 [n_sel]
  *   wqkv        device bf16 [(n_q_heads + 2 n_kv_heads) * head_dim, hidden]: one row per
@@ -164,6 +165,61 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
  * size (0 on invalid arguments). */
 size_t ct_workspace_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel);
 
+/* ---- The rest of a transformer layer on the selected rows, and the multi-layer partial prefill.
+ * After the check layer every layer of the model runs on the selected tokens only (Sec. 4.2,
+ * fusion layers); the non-selected tokens contribute their cached K/V and nothing else. ---- */
+
+/* out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + eps) * weight, fp32 arithmetic, bf16 in and out.
+ *   x, out device bf16 [n_tokens, width] (out may equal x); weight device bf16 [width];
+ *   width a multiple of 8. */
+ct_status ct_rmsnorm(const void* x, const void* weight, float eps, int32_t n_tokens, int32_t width, void* out,
+                     void* stream);
+
+/* out[t,:] = x[t,:] * w^T (+ residual[t,:]), bf16 MFMA, fp32 accumulation, bf16 result.
+ *   x device bf16 [n_tokens, k_len]; w device bf16 [n_out, k_len] (one row per output feature);
+ *   residual device bf16 [n_tokens, n_out] or NULL; out device bf16 [n_tokens, n_out], may equal
+ *   residual (each element is read before it is written), may not overlap x.
+ *   k_len and n_out multiples of 64. */
+ct_status ct_linear(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out, const void* residual,
+                    void* out, void* stream);
+
+/* out[t,:] = silu(x[t,:] * w_gate^T) * (x[t,:] * w_up^T) (SwiGLU), one kernel, bf16 result.
+ *   w_gate, w_up device bf16 [n_out, k_len]; out device bf16 [n_tokens, n_out]. */
+ct_status ct_swiglu(const void* x, int32_t n_tokens, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
+                    void* out, void* stream);
+
+/* Weights and cached KV of one layer.  All weights device bf16, one row per output feature:
+ * attn_norm, ffn_norm [hidden]; wqkv [(n_q_heads + 2 n_kv_heads) head_dim, hidden];
+ * wo [hidden, n_q_heads head_dim]; w_gate, w_up [ffn_dim, hidden]; w_down [hidden, ffn_dim].
+ * chunks: this layer's n_chunks cached KV chunks (same token counts and positions in every
+ * layer; k / v may be NULL when every row is recomputed). */
+typedef struct {
+  const void* attn_norm;
+  const void* wqkv;
+  const void* wo;
+  const void* ffn_norm;
+  const void* w_gate;
+  const void* w_up;
+  const void* w_down;
+  const ct_chunk* chunks;
+} ct_layer_weights;
+
+/* Partial prefill of n_layers layers on the selected rows (pre-norm blocks: RMSNorm, selected
+ * attention over the fused KV, output projection + residual, RMSNorm, SwiGLU FFN + residual).
+ *   hidden_sel device bf16 [n_sel, hidden]: in, the layer-0 input rows of the selected tokens
+ *              (compact, in sel_idx order); out, the last layer's output rows.
+ *   k_bufs, v_bufs device bf16 [2, n_ctx, n_kv_heads, head_dim]: two layer buffers used in
+ *              turn, so that layer l+1's pinned-host chunks are copied on copy_stream while
+ *              layer l computes.  On return slot (n_layers-1) % 2 holds the last layer's fused KV.
+ *   n_sel == n_ctx is ordinary full prefill: no cached KV is read or copied.
+ *   workspace  at least ct_stack_workspace_bytes() bytes, 256-byte aligned.
+ * Events are taken from a process-wide pool: concurrent stack calls are not supported. */
+ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, float rms_eps, const ct_layer_weights* layers,
+                                   int32_t n_layers, int32_t n_chunks, void* hidden_sel, const int32_t* sel_idx,
+                                   int32_t n_sel, double recompute_ratio, void* k_bufs, void* v_bufs, void* workspace,
+                                   size_t workspace_bytes, void* compute_stream, void* copy_stream);
+size_t ct_stack_workspace_bytes(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx, int32_t n_sel);
+
 /* Host-side check of an index set: strictly ascending and inside [0, n_ctx). */
 ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_ctx);
 
@@ -172,7 +228,8 @@ ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_
  * ct_profile_read waits for the recorded events of one kernel class, adds their elapsed
  * times and returns the number of launches and the summed milliseconds; ct_profile_reset
  * forgets what was recorded.  Classes: 0 qkv projection, 1 re-RoPE, 2 scatter,
- * 3 selected attention (main kernel), 4 attention split merge.  Profiling is process wide,
+ * 3 selected attention (main kernel), 4 attention split merge, 5 linear / SwiGLU GEMMs,
+ * 6 RMSNorm.  Profiling is process wide,
  * off by default, creates events on first use and is not meant for concurrent callers. */
 void ct_set_profiling(int32_t on);
 void ct_profile_reset(void);

@@ -21,6 +21,12 @@ intermediate rounding:
   selected_attention  the check/fusion-layer attention "only for the corresponding tokens":
                       causal softmax attention of the selected queries over the fused KV.
   partial_prefill_layer  the composition of the four.
+  rmsnorm, swiglu_ffn, layer_tail, partial_prefill_stack
+                      the rest of a pre-norm transformer layer applied to the selected rows
+                      only (Sec. 4.2: every layer after the check layer is a fusion layer that
+                      works on the selected tokens) and the chain of layers.  The paper names
+                      the models (Sec. 5) but not these formulas; they are the standard RMSNorm
+                      and SwiGLU definitions of those models.
 
 Readings where the paper is silent (RoPE pair convention and frequencies, softmax scale,
 GQA head mapping, floor for r*N, V being position independent) are stated at the function
@@ -181,3 +187,55 @@ def partial_prefill_layer(hidden_sel, wqkv, bias, k_cache, v_cache, old_pos, new
     k_fused, v_fused = scatter_kv(k_rot, np.asarray(v_cache, dtype=np.float64), k_new, v_new, sel_idx)
     out, lse = selected_attention(q, k_fused, v_fused, sel_idx, rows=rows)
     return out, lse, k_fused, v_fused
+
+
+# ----------------------------------------------------------------------------- step a7
+def rmsnorm(x, weight, eps):
+    """y = x / sqrt(mean(x^2) + eps) * weight over the last axis."""
+    x = np.asarray(x, dtype=np.float64)
+    ms = (x * x).mean(axis=-1, keepdims=True)
+    return x / np.sqrt(ms + np.float64(eps)) * np.asarray(weight, dtype=np.float64)
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def swiglu_ffn(x, w_gate, w_up, w_down):
+    """(silu(x Wg^T) * (x Wu^T)) Wd^T with weights stored one row per output feature."""
+    x = np.asarray(x, dtype=np.float64)
+    g = x @ np.asarray(w_gate, dtype=np.float64).T
+    u = x @ np.asarray(w_up, dtype=np.float64).T
+    return (silu(g) * u) @ np.asarray(w_down, dtype=np.float64).T
+
+
+def layer_tail(h, attn_out, wo, ffn_norm, w_gate, w_up, w_down, eps):
+    """Output projection + residual, then RMSNorm -> SwiGLU FFN + residual.
+    h: [n, E] layer input rows; attn_out: [n, Hq, D]."""
+    h = np.asarray(h, dtype=np.float64)
+    a = np.asarray(attn_out, dtype=np.float64).reshape(h.shape[0], -1)
+    h1 = h + a @ np.asarray(wo, dtype=np.float64).T
+    return h1 + swiglu_ffn(rmsnorm(h1, ffn_norm, eps), w_gate, w_up, w_down)
+
+
+def transformer_layer(h_sel, lw, old_pos, new_pos, sel_idx, n_q_heads, n_kv_heads, head_dim, theta, eps,
+                      style: int = HALF_SPLIT):
+    """One layer on the selected rows.  lw: dict with attn_norm, wqkv, wo, ffn_norm, w_gate, w_up,
+    w_down, k_cache, v_cache.  Returns (output rows, fused K, fused V)."""
+    x = rmsnorm(h_sel, lw["attn_norm"], eps)
+    attn, _, kf, vf = partial_prefill_layer(x, lw["wqkv"], None, lw["k_cache"], lw["v_cache"], old_pos, new_pos,
+                                            sel_idx, n_q_heads, n_kv_heads, head_dim, theta, style)
+    return layer_tail(h_sel, attn, lw["wo"], lw["ffn_norm"], lw["w_gate"], lw["w_up"], lw["w_down"], eps), kf, vf
+
+
+def partial_prefill_stack(h_sel, layers, old_pos, new_pos, sel_idx, n_q_heads, n_kv_heads, head_dim, theta, eps,
+                          style: int = HALF_SPLIT, keep_inputs: bool = False):
+    """Chain of layers on the selected rows; the same index set in every layer.
+    Returns the last layer's output rows (and, with keep_inputs, the list of per-layer inputs)."""
+    h = np.asarray(h_sel, dtype=np.float64)
+    inputs = []
+    for lw in layers:
+        if keep_inputs:
+            inputs.append(h)
+        h, _, _ = transformer_layer(h, lw, old_pos, new_pos, sel_idx, n_q_heads, n_kv_heads, head_dim, theta, eps, style)
+    return (h, inputs) if keep_inputs else h

@@ -18,12 +18,13 @@ CT_OK = 0
 CT_ERR_NULL, CT_ERR_SHAPE, CT_ERR_INDEX, CT_ERR_RATIO = -1, -2, -3, -4
 CT_ERR_WORKSPACE, CT_ERR_HIP, CT_ERR_UNSUPPORTED = -5, -6, -7
 
-KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 4}
+KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 4, "linear": 5, "norm": 6}
 
 EXPORTS = [
     "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
     "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
+    "ct_rmsnorm", "ct_linear", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
 ]
 
 
@@ -35,6 +36,11 @@ class LayerCfg(ctypes.Structure):
 class Chunk(ctypes.Structure):
     _fields_ = [("k", c_void_p), ("v", c_void_p), ("n_tokens", c_int32), ("old_pos_start", c_int32),
                 ("new_pos_start", c_int32), ("location", c_int32), ("raw_keys", c_int32), ("reserved", c_int32)]
+
+
+class LayerWeights(ctypes.Structure):
+    _fields_ = [("attn_norm", c_void_p), ("wqkv", c_void_p), ("wo", c_void_p), ("ffn_norm", c_void_p),
+                ("w_gate", c_void_p), ("w_up", c_void_p), ("w_down", c_void_p), ("chunks", POINTER(Chunk))]
 
 
 class CacheTuneError(RuntimeError):
@@ -66,6 +72,13 @@ def load() -> ctypes.CDLL:
     lib.ct_selected_attention.argtypes = [cfgp, P, P, P, c_int32, P, c_int32, P, P, P, c_size_t, P]
     lib.ct_partial_prefill_layer.argtypes = [cfgp, POINTER(Chunk), c_int32, P, P, P, c_int32, c_double, P, P,
                                              P, P, P, P, c_size_t, P, P]
+    lib.ct_rmsnorm.argtypes = [P, P, c_float, c_int32, c_int32, P, P]
+    lib.ct_linear.argtypes = [P, c_int32, c_int32, P, c_int32, P, P, P]
+    lib.ct_swiglu.argtypes = [P, c_int32, c_int32, P, P, c_int32, P, P]
+    lib.ct_partial_prefill_stack.argtypes = [cfgp, c_int32, c_float, POINTER(LayerWeights), c_int32, c_int32, P, P,
+                                             c_int32, c_double, P, P, P, c_size_t, P, P]
+    lib.ct_stack_workspace_bytes.argtypes = [cfgp, c_int32, c_int32, c_int32]
+    lib.ct_stack_workspace_bytes.restype = c_size_t
     lib.ct_workspace_bytes.argtypes = [cfgp, c_int32, c_int32]
     lib.ct_workspace_bytes.restype = c_size_t
     lib.ct_validate_indices.argtypes = [P, c_int32, c_int32]
@@ -77,7 +90,8 @@ def load() -> ctypes.CDLL:
     lib.ct_last_error.restype = c_char_p
     lib.ct_version.restype = c_char_p
     for name in ("ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
-                 "ct_partial_prefill_layer", "ct_validate_indices", "ct_profile_read"):
+                 "ct_partial_prefill_layer", "ct_validate_indices", "ct_profile_read", "ct_rmsnorm", "ct_linear",
+                 "ct_swiglu", "ct_partial_prefill_stack"):
         getattr(lib, name).restype = c_int32
     _lib = lib
     return lib
@@ -178,6 +192,45 @@ def ct_partial_prefill_layer(cfg, chunks, n_chunks, hidden, hidden_rows, sel_idx
                                            _ptr(sel_idx), n_sel, float(recompute_ratio), _ptr(wqkv), _ptr(bias),
                                            _ptr(k_buf), _ptr(v_buf), _ptr(attn_out), _ptr(workspace),
                                            workspace_bytes, _stream(compute_stream), _stream(copy_stream)))
+
+
+def ct_rmsnorm(x, weight, eps, n_tokens, width, out, stream=None) -> None:
+    _check(load().ct_rmsnorm(_ptr(x), _ptr(weight), float(eps), n_tokens, width, _ptr(out), _stream(stream)))
+
+
+def ct_linear(x, n_tokens, k_len, w, n_out, residual, out, stream=None) -> None:
+    _check(load().ct_linear(_ptr(x), n_tokens, k_len, _ptr(w), n_out, _ptr(residual), _ptr(out), _stream(stream)))
+
+
+def ct_swiglu(x, n_tokens, k_len, w_gate, w_up, n_out, out, stream=None) -> None:
+    _check(load().ct_swiglu(_ptr(x), n_tokens, k_len, _ptr(w_gate), _ptr(w_up), n_out, _ptr(out), _stream(stream)))
+
+
+def make_layers(entries: Sequence[dict]):
+    """entries: dicts with attn_norm, wqkv, wo, ffn_norm, w_gate, w_up, w_down (tensors) and
+    chunks (a Chunk array from make_chunks).  The returned array keeps the chunk arrays alive."""
+    arr = (LayerWeights * len(entries))()
+    keep = []
+    for i, e in enumerate(entries):
+        keep.append(e["chunks"])
+        arr[i] = LayerWeights(_ptr(e["attn_norm"]), _ptr(e["wqkv"]), _ptr(e["wo"]), _ptr(e["ffn_norm"]),
+                              _ptr(e["w_gate"]), _ptr(e["w_up"]), _ptr(e["w_down"]),
+                              ctypes.cast(e["chunks"], POINTER(Chunk)))
+    arr._keep = keep
+    return arr
+
+
+def ct_stack_workspace_bytes(cfg: LayerCfg, ffn_dim: int, n_ctx: int, n_sel: int) -> int:
+    return int(load().ct_stack_workspace_bytes(byref(cfg), ffn_dim, n_ctx, n_sel))
+
+
+def ct_partial_prefill_stack(cfg, ffn_dim, rms_eps, layers, n_layers, n_chunks, hidden_sel, sel_idx, n_sel,
+                             recompute_ratio, k_bufs, v_bufs, workspace, workspace_bytes, compute_stream=None,
+                             copy_stream=None) -> None:
+    _check(load().ct_partial_prefill_stack(byref(cfg), ffn_dim, float(rms_eps), layers, n_layers, n_chunks,
+                                           _ptr(hidden_sel), _ptr(sel_idx), n_sel, float(recompute_ratio),
+                                           _ptr(k_bufs), _ptr(v_bufs), _ptr(workspace), workspace_bytes,
+                                           _stream(compute_stream), _stream(copy_stream)))
 
 
 def ct_set_profiling(on: bool) -> None:

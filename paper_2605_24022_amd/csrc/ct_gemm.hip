@@ -1,0 +1,421 @@
+// The bf16 MFMA GEMM of the selected rows with fused epilogues:
+//   - selective recompute of Q, K, V (Eq. 1) with RoPE at the rows' true positions
+//     (Sec. 4.2, last paragraph);
+//   - the other linear maps a transformer layer applies to the selected rows only
+//     (Sec. 4.2: every layer after the check layer works on the selected tokens): output
+//     projection and FFN down projection with the residual added, and the SwiGLU gate/up pair.
+//
+// The kernel computes the transposed product  C^T[f, t] = sum_e W[f, e] * X[row(t), e]
+// (features in the MFMA M dimension, tokens in N) so that, in the 32x32 accumulator layout,
+// a lane holds one token (column) and groups of four consecutive features (rows):
+//   - both elements of every RoPE pair of a token sit in the same lane (no cross-lane
+//     traffic in the epilogue), and the token's position is a per-lane scalar;
+//   - results leave as 8-byte stores of four consecutive bf16 features.
+// Both operands are K-contiguous in memory (W is out-features major, X is token major).
+// Tiles go from global memory straight into LDS (global_load_lds_dwordx4, no register
+// staging): a wave-wide load fills 8 rows of 128 bytes, the 16-byte pieces of a row are
+// XOR-swizzled so that the 128-bit fragment reads of 16 consecutive rows hit distinct banks.
+//
+// Workgroup: 512 threads = 8 waves (2 feature halves x 4 token quarters), tile 256 features x
+// 256 tokens x 64 (K step), wave tile 128 x 64 = 4 x 2 MFMA tiles of
+// v_mfma_f32_32x32x16_bf16, two LDS stages of 64 KiB, one barrier per K step.  Two waves
+// share a SIMD, so one wave's fragment reads and waits hide behind the other's MFMAs.
+// Workgroups are numbered so that the ones resident on one XCD (ids congruent mod 8) cover a
+// patch of neighbouring tiles and share their W and X tiles in that XCD's L2.
+#include <string.h>
+
+#include "ct_internal.h"
+
+namespace ct {
+
+namespace {
+
+constexpr int BF = 256;           // features per workgroup
+constexpr int BT = 256;           // tokens per workgroup
+constexpr int BK = 64;            // reduction elements per stage
+constexpr int ROWB = BK * 2;      // LDS row in bytes (unpadded, swizzled)
+constexpr int A_BYTES = BF * ROWB;
+constexpr int B_BYTES = BT * ROWB;
+constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int NWAVES = 8;
+constexpr int A_LOADS = BF / 8 / NWAVES;   // wave-wide loads (8 rows each) per wave and stage
+constexpr int B_LOADS = BT / 8 / NWAVES;
+
+enum Epilogue { EPI_QKV_ROPE = 0, EPI_LINEAR = 1, EPI_SWIGLU = 2 };
+
+struct GemmArgs {
+  const uint16_t* hidden;        // B operand X [*, E], token major
+  const int32_t* hidden_rows;    // optional row gather
+  const uint16_t* wqkv;          // A operand W [O, E], feature major (SwiGLU: the gate matrix)
+  const uint16_t* w_up;          // SwiGLU only: the up matrix [O, E]
+  int32_t n_sel, E, O;           // tokens, reduction length, features (rows of W)
+  int32_t nF, nT;                // tiles
+  // EPI_QKV_ROPE
+  const int32_t* sel_pos;
+  const int32_t* sel_idx;
+  const uint16_t* bias;
+  uint16_t* q_out;
+  uint16_t* k_out;
+  uint16_t* v_out;
+  int32_t Hq, Hkv;
+  // EPI_LINEAR / EPI_SWIGLU: out[t, f] (+ residual[t, f]), row length O
+  const uint16_t* residual;
+  uint16_t* out;
+};
+typedef GemmArgs QkvArgs;
+
+__device__ __forceinline__ int32_t position_of_row(const ChunkTable& tab, int32_t r) {
+  int c = 0;
+  while (c + 1 < tab.n && r >= tab.row_start[c + 1]) ++c;
+  return tab.new_start[c] + (r - tab.row_start[c]);
+}
+
+// swizzle of the 16-byte pieces of LDS row r (rows are 128 bytes: two rows per 256-byte bank span)
+__device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
+
+// EPI_SWIGLU: the 128 A rows of a wave are 64 gate rows followed by the 64 up rows of the same
+// output features, so gate and up of one (feature, token) land in the same lane and register
+// index of accumulator tiles (m, m + 2) - the same pairing the half-split RoPE uses.
+template <int EPI, int D, int STYLE>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_kernel(GemmArgs a, RopeTable rope,
+                                                                                             ChunkTable chunks) {
+  __shared__ __align__(1024) unsigned char lds[2 * STAGE_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hi = lane >> 5;
+
+  // ---- workgroup -> tile, XCD aware (consecutive ids go to different XCDs) ----------------
+  const int total = a.nF * a.nT;
+  const int per_xcd = (total + 7) / 8;
+  const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (v >= total) return;
+  constexpr int PF = 4, PT = 8;
+  const int tp = v / (PT * a.nF);
+  const int rem = v - tp * PT * a.nF;
+  const int th = min(PT, a.nT - tp * PT);
+  const int fp = rem / (PF * th);
+  const int r2 = rem - fp * PF * th;
+  const int fw = min(PF, a.nF - fp * PF);
+  const int f_blk = (fp * PF + r2 % fw) * (EPI == EPI_SWIGLU ? BF / 2 : BF);   // first output feature
+  const int t_blk = (tp * PT + r2 / fw) * BT;
+
+  // ---- global -> LDS loads -------------------------------------------------------------------
+  // load j of this wave fills LDS rows (NWAVES * j + wave) * 8 .. + 7 of the A (or B) tile; this
+  // lane supplies physical piece lane % 8 of row lane / 8, i.e. logical piece (that ^ swizzle).
+  // Byte offsets from the tensor bases fit 32 bits (checked on the host); the K step advances
+  // the scalar base, so the per-lane offsets are loop invariant.
+  uint32_t a_off[A_LOADS], b_off[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int row = (NWAVES * j + wave) * 8 + (lane >> 3);
+    // SwiGLU: tile row -> (wave half, gate | up, feature within the wave's 64)
+    const int frow = EPI == EPI_SWIGLU ? f_blk + (row >> 7) * 64 + (row & 63) : f_blk + row;
+    const int f = min(frow, a.O - 1);
+    a_off[j] = ((uint32_t)f * a.E + (((lane & 7) ^ swz(row)) * 8)) * 2;
+  }
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    const int row = (NWAVES * j + wave) * 8 + (lane >> 3);
+    const int t = min(t_blk + row, a.n_sel - 1);
+    const uint32_t xr = a.hidden_rows ? (uint32_t)a.hidden_rows[t] : (uint32_t)t;
+    b_off[j] = (xr * a.E + (((lane & 7) ^ swz(row)) * 8)) * 2;
+  }
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  const uint32_t lds_addr0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  auto dma16 = [&](const uint16_t* base, uint32_t byte_off, uint32_t lds_addr) __attribute__((always_inline)) {
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(base) : "memory");
+  };
+  auto issue_stage = [&](int k0, int stage) __attribute__((always_inline)) {
+    const uint16_t* wk = a.wqkv + k0;      // scalar bases advanced to the K step
+    const uint16_t* uk = EPI == EPI_SWIGLU ? a.w_up + k0 : wk;
+    const uint16_t* xk = a.hidden + k0;
+    const uint32_t st = lds_addr0 + stage * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) {
+      // a wave-wide load covers 8 consecutive tile rows: all gate or all up
+      const bool up = EPI == EPI_SWIGLU && ((((NWAVES * j + wave) * 8) >> 6) & 1);
+      dma16(up ? uk : wk, a_off[j], st + (NWAVES * j + wave) * 1024);
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) dma16(xk, b_off[j], st + A_BYTES + (NWAVES * j + wave) * 1024);
+  };
+
+  const int wf = wave & 1, wt = wave >> 1;
+  // fragment read offsets inside a stage (bytes): row base + swizzled piece, per k-step
+  int a_frag[BK / 16], b_frag[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) {
+    a_frag[ks] = (wf * 128 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+    b_frag[ks] = A_BYTES + (wt * 64 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+  }
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
+
+  const int nk = a.E / BK;
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // ordinary loads so far (row indices) are complete
+  issue_stage(0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's part of stage kt has landed
+    __syncthreads();                      // everybody's has; everybody is done reading the other stage
+    if (kt + 1 < nk) issue_stage((kt + 1) * BK, buf ^ 1);
+    const unsigned char* base = lds + buf * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[4], fb[2];
+#pragma unroll
+      for (int m = 0; m < 4; ++m) fa[m] = *reinterpret_cast<const bf16x8*>(base + a_frag[ks] + m * 32 * ROWB);
+#pragma unroll
+      for (int n = 0; n < 2; ++n) fb[n] = *reinterpret_cast<const bf16x8*>(base + b_frag[ks] + n * 32 * ROWB);
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+    }
+  }
+
+  // ---- epilogues ---------------------------------------------------------------------------------
+  // accumulator element i of tile (m, n): row f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
+  if constexpr (EPI == EPI_LINEAR) {
+    const int f0 = f_blk + wf * 128;
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int t = t_blk + wt * 64 + n * 32 + l32;
+      if (t >= a.n_sel) continue;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const int fm = f0 + m * 32;
+        if (fm >= a.O) continue;
+        const size_t row = (size_t)t * a.O + fm + 4 * hi;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v0 = acc[m][n][4 * g + 0], v1 = acc[m][n][4 * g + 1], v2 = acc[m][n][4 * g + 2], v3 = acc[m][n][4 * g + 3];
+          if (a.residual != nullptr) {
+            const u32x2 r = *reinterpret_cast<const u32x2*>(a.residual + row + 8 * g);
+            v0 += bf16_lo(r[0]); v1 += bf16_hi(r[0]); v2 += bf16_lo(r[1]); v3 += bf16_hi(r[1]);
+          }
+          u32x2 w;
+          w[0] = pack_bf16(v0, v1);
+          w[1] = pack_bf16(v2, v3);
+          *reinterpret_cast<u32x2*>(a.out + row + 8 * g) = w;
+        }
+      }
+    }
+    return;
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    const int f0 = f_blk + wf * 64;          // output features of this wave: f0 .. f0 + 63
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int t = t_blk + wt * 64 + n * 32 + l32;
+      if (t >= a.n_sel) continue;
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {          // gate tile m, up tile m + 2
+        const int fm = f0 + m * 32;
+        if (fm >= a.O) continue;
+        const size_t row = (size_t)t * a.O + fm + 4 * hi;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v[4];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const float gate = acc[m][n][4 * g + b], up = acc[m + 2][n][4 * g + b];
+            v[b] = gate / (1.0f + __builtin_amdgcn_exp2f(-gate * 1.4426950408889634f)) * up;   // silu(gate) * up
+          }
+          u32x2 w;
+          w[0] = pack_bf16(v[0], v[1]);
+          w[1] = pack_bf16(v[2], v[3]);
+          *reinterpret_cast<u32x2*>(a.out + row + 8 * g) = w;
+        }
+      }
+    }
+    return;
+  } else {
+    // accumulator element i of tile (m, n): feature f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
+    const int f0 = f_blk + wf * 128;
+    const int rope_end = (a.Hq + a.Hkv) * D;   // features below this are q or k heads
+    const int q_end = a.Hq * D;
+  #pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int t = t_blk + wt * 64 + n * 32 + l32;
+      const bool t_ok = t < a.n_sel;
+      const int tc = t_ok ? t : a.n_sel - 1;
+      const int32_t pos = a.sel_pos ? a.sel_pos[tc] : position_of_row(chunks, a.sel_idx[tc]);
+
+      if (a.bias != nullptr) {
+  #pragma unroll
+        for (int m = 0; m < 4; ++m)
+  #pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int f = min(f0 + m * 32 + 8 * (i >> 2) + 4 * hi + (i & 3), a.O - 1);
+            acc[m][n][i] += bf16_lo((uint32_t)a.bias[f]);
+          }
+      }
+
+      if (STYLE == 0) {
+        // pairs (j, j + D/2): D = 128 couples tiles (m, m+2); D = 64 couples (m, m+1) for m even
+        constexpr int STEP = D / 64;          // tile distance between the two halves of a pair
+  #pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          if ((D == 128 && m >= 2) || (D == 64 && (m & 1))) continue;
+          const int fa0 = f0 + m * 32;        // first feature of the "a" half tile
+          if (fa0 >= rope_end) continue;      // v heads are not rotated
+  #pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int j = (fa0 % D) + 8 * (i >> 2) + 4 * hi + (i & 3);
+            float c, s;
+            sincos_turns(pos, rope.turns[j], c, s);
+            const float x = acc[m][n][i], y = acc[m + STEP][n][i];
+            acc[m][n][i] = x * c - y * s;
+            acc[m + STEP][n][i] = x * s + y * c;
+          }
+        }
+      } else {
+  #pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const int fa0 = f0 + m * 32;
+          if (fa0 >= rope_end) continue;
+  #pragma unroll
+          for (int i = 0; i < 16; i += 2) {
+            const int j = ((fa0 % D) + 8 * (i >> 2) + 4 * hi + (i & 3)) >> 1;
+            float c, s;
+            sincos_turns(pos, rope.turns[j], c, s);
+            const float x = acc[m][n][i], y = acc[m][n][i + 1];
+            acc[m][n][i] = x * c - y * s;
+            acc[m][n][i + 1] = x * s + y * c;
+          }
+        }
+      }
+
+      if (!t_ok) continue;
+  #pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const int fm = f0 + m * 32;
+        if (fm >= a.O) continue;
+        uint16_t* dst;
+        if (fm < q_end)
+          dst = a.q_out + (size_t)t * q_end + fm;
+        else if (fm < rope_end)
+          dst = a.k_out + (size_t)t * (a.Hkv * D) + (fm - q_end);
+        else
+          dst = a.v_out + (size_t)t * (a.Hkv * D) + (fm - rope_end);
+  #pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w;
+          w[0] = pack_bf16(acc[m][n][4 * g + 0], acc[m][n][4 * g + 1]);
+          w[1] = pack_bf16(acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]);
+          *reinterpret_cast<u32x2*>(dst + 8 * g + 4 * hi) = w;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+static void fill_tiles(GemmArgs* a, bool swiglu) {
+  a->nF = (a->O + (swiglu ? BF / 2 : BF) - 1) / (swiglu ? BF / 2 : BF);
+  a->nT = (a->n_sel + BT - 1) / BT;
+}
+
+template <typename Kernel>
+static ct_status launch_gemm(Kernel kernel, const GemmArgs& a, const RopeTable& rope, const ChunkTable& tab,
+                             KernelClass kc, hipStream_t s) {
+  const int total = a.nF * a.nT;
+  const int per_xcd = (total + 7) / 8;
+  dim3 grid(per_xcd * 8), block(512);
+  int slot = prof_begin(kc, s);
+  hipLaunchKernelGGL(kernel, grid, block, 0, s, a, rope, tab);
+  prof_end(kc, slot, s);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, "gemm kernel launch");
+  return CT_OK;
+}
+
+ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
+                     const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
+                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s) {
+  if (n_sel == 0) return CT_OK;
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.hidden = static_cast<const uint16_t*>(hidden);
+  a.hidden_rows = hidden_rows;
+  a.sel_pos = sel_pos;
+  a.sel_idx = sel_idx;
+  a.wqkv = static_cast<const uint16_t*>(wqkv);
+  a.bias = static_cast<const uint16_t*>(bias);
+  a.q_out = static_cast<uint16_t*>(q_out);
+  a.k_out = static_cast<uint16_t*>(k_out);
+  a.v_out = static_cast<uint16_t*>(v_out);
+  a.n_sel = n_sel;
+  a.E = cfg->hidden;
+  a.Hq = cfg->n_q_heads;
+  a.Hkv = cfg->n_kv_heads;
+  a.O = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+  fill_tiles(&a, false);
+  RopeTable rope;
+  fill_rope_table(cfg, &rope);
+  ChunkTable tab;
+  if (chunks != nullptr) {
+    tab = *chunks;
+  } else {
+    tab.n = 1;
+    tab.row_start[0] = 0;
+    tab.row_start[1] = 0x7fffffff;
+    tab.new_start[0] = 0;
+  }
+  if (cfg->head_dim == 128)
+    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0>, a, rope, tab, KC_QKV, s)
+                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1>, a, rope, tab, KC_QKV, s);
+  return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0>, a, rope, tab, KC_QKV, s)
+                              : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1>, a, rope, tab, KC_QKV, s);
+}
+
+ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
+                        void* out, hipStream_t s) {
+  if (n_tok == 0) return CT_OK;
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.hidden = static_cast<const uint16_t*>(x);
+  a.wqkv = static_cast<const uint16_t*>(w);
+  a.residual = static_cast<const uint16_t*>(residual);
+  a.out = static_cast<uint16_t*>(out);
+  a.n_sel = n_tok;
+  a.E = k_len;
+  a.O = n_out;
+  fill_tiles(&a, false);
+  RopeTable rope;
+  memset(&rope, 0, sizeof(rope));
+  ChunkTable tab;
+  memset(&tab, 0, sizeof(tab));
+  return launch_gemm(gemm_kernel<EPI_LINEAR, 128, 0>, a, rope, tab, KC_LINEAR, s);
+}
+
+ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
+                        void* out, hipStream_t s) {
+  if (n_tok == 0) return CT_OK;
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.hidden = static_cast<const uint16_t*>(x);
+  a.wqkv = static_cast<const uint16_t*>(w_gate);
+  a.w_up = static_cast<const uint16_t*>(w_up);
+  a.out = static_cast<uint16_t*>(out);
+  a.n_sel = n_tok;
+  a.E = k_len;
+  a.O = n_out;
+  fill_tiles(&a, true);
+  RopeTable rope;
+  memset(&rope, 0, sizeof(rope));
+  ChunkTable tab;
+  memset(&tab, 0, sizeof(tab));
+  return launch_gemm(gemm_kernel<EPI_SWIGLU, 128, 0>, a, rope, tab, KC_LINEAR, s);
+}
+
+}  // namespace ct

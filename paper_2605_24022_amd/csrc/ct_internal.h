@@ -9,7 +9,7 @@
 namespace ct {
 
 // ---- kernel classes for the opt-in event profiling ------------------------------------
-enum KernelClass { KC_QKV = 0, KC_REROPE = 1, KC_SCATTER = 2, KC_ATTN = 3, KC_MERGE = 4, KC_COUNT = 5 };
+enum KernelClass { KC_QKV = 0, KC_REROPE = 1, KC_SCATTER = 2, KC_ATTN = 3, KC_MERGE = 4, KC_LINEAR = 5, KC_NORM = 6, KC_COUNT = 7 };
 
 ct_status fail(ct_status code, const char* fmt, ...);
 ct_status hip_fail(hipError_t e, const char* what);
@@ -67,6 +67,14 @@ struct ChunkTable {
 ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
                      const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
                      const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s);
+// out[t, :] = x[t, :] * w^T (+ residual[t, :]);  x [n_tok, k_len], w [n_out, k_len], bf16
+ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
+                        void* out, hipStream_t s);
+// out[t, :] = silu(x[t, :] * w_gate^T) * (x[t, :] * w_up^T);  both weights [n_out, k_len]
+ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
+                        void* out, hipStream_t s);
+// out[t, :] = x[t, :] / sqrt(mean(x[t, :]^2) + eps) * w;  x, out [n_tok, width] bf16, w [width] bf16
+ct_status launch_rmsnorm(const void* x, const void* w, float eps, int32_t n_tok, int32_t width, void* out, hipStream_t s);
 ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
                            int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
                            void* workspace, hipStream_t s);

@@ -244,3 +244,57 @@ def sample_rows(n_sel: int, count: int, seed: int = 0) -> np.ndarray:
     pick = set([0, 1, n_sel // 2, n_sel - 2, n_sel - 1])
     pick.update(rng.choice(n_sel, size=count - len(pick), replace=False).tolist())
     return np.array(sorted(pick))[:count].astype(np.int64)
+
+
+# --------------------------------------------------------------------------- multi-layer stack
+@dataclass
+class StackWorkload:
+    spec: WorkloadSpec
+    ffn_dim: int
+    rms_eps: float
+    hidden0: np.ndarray          # uint16 [n_sel, E]: layer-0 input rows of the selected tokens
+    layers: list                 # per layer: dict of uint16 arrays (attn_norm, wqkv, wo, ffn_norm, w_gate, w_up, w_down, k_cache, v_cache)
+    old_pos: np.ndarray
+    new_pos: np.ndarray
+    sel_idx: np.ndarray
+    chunk_rows: np.ndarray
+    chunk_new_start: np.ndarray
+
+
+def make_stack_workload(sp: WorkloadSpec, n_layers: int, ffn_dim: int, rms_eps: float = 1e-5,
+                        unit_norm_weights: bool = False) -> StackWorkload:
+    """Per layer (streams 100*l + k of the spec's seed): 0 attn_norm, 1 wqkv ~ N(0,1)/sqrt(E),
+    2 wo ~ N(0,1)/sqrt(Hq*D), 3 ffn_norm, 4 w_gate, 5 w_up ~ N(0,1)/sqrt(E), 6 w_down ~ N(0,1)/sqrt(F),
+    7 K cache, 8 V cache ~ N(0,1); norm weights are 1 (or 1 + 0.1 N(0,1) to exercise the multiply).
+    Stream 0 of the spec's seed gives the layer-0 input rows."""
+    sh = sp.shape
+    E, qd = sh.hidden, sh.n_q_heads * sh.head_dim
+    n_ctx = sp.n_ctx
+    sel = select_indices(sp)
+
+    def norm_w(stream):
+        if unit_norm_weights:
+            return f32_to_bf16_bits(np.ones(E, dtype=np.float32))
+        rng = np.random.default_rng([sp.seed, stream])
+        return f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(E)).astype(np.float32))
+
+    layers = []
+    for l in range(n_layers):
+        b = 100 * (l + 1)
+        layers.append(dict(
+            attn_norm=norm_w(b + 0),
+            wqkv=_normal_bf16(sp.seed, b + 1, (sh.qkv_width, E), 1.0 / np.sqrt(E)),
+            wo=_normal_bf16(sp.seed, b + 2, (E, qd), 1.0 / np.sqrt(qd)),
+            ffn_norm=norm_w(b + 3),
+            w_gate=_normal_bf16(sp.seed, b + 4, (ffn_dim, E), 1.0 / np.sqrt(E)),
+            w_up=_normal_bf16(sp.seed, b + 5, (ffn_dim, E), 1.0 / np.sqrt(E)),
+            w_down=_normal_bf16(sp.seed, b + 6, (E, ffn_dim), 1.0 / np.sqrt(ffn_dim)),
+            k_cache=_normal_bf16(sp.seed, b + 7, (n_ctx, sh.n_kv_heads, sh.head_dim)),
+            v_cache=_normal_bf16(sp.seed, b + 8, (n_ctx, sh.n_kv_heads, sh.head_dim)),
+        ))
+    i = np.arange(n_ctx, dtype=np.int32)
+    c = np.arange(sp.n_chunks, dtype=np.int32)
+    return StackWorkload(sp, ffn_dim, rms_eps, _normal_bf16(sp.seed, 0, (sel.size, E)), layers,
+                         (i % sp.chunk_len).astype(np.int32), i.copy(), sel,
+                         np.concatenate([c * sp.chunk_len, [n_ctx]]).astype(np.int32),
+                         (c * sp.chunk_len).astype(np.int32))

@@ -52,9 +52,17 @@ def errors(got: np.ndarray, want: np.ndarray):
     return max_abs, rel
 
 
-def assert_close(got, want, what, max_abs=MAX_ABS, rel_l2=ROW_REL_L2):
+def assert_close(got, want, what, max_abs=MAX_ABS, rel_l2=ROW_REL_L2, ulp_slack=0.0):
+    """max-abs and per-row relative L2 bounds.  `ulp_slack` > 0 lets the absolute bound grow with
+    the magnitude of the expected value (|err| <= max_abs + ulp_slack * |want|): a bf16 result
+    above 8 in magnitude is rounded with a spacing of 2^-5 or more, which alone exceeds 2e-2."""
     assert np.isfinite(np.asarray(got)).all(), f"{what}: non-finite values in the GPU result"
-    ma, rl = errors(got, want)
-    print(f"[parity] {what}: max-abs {ma:.3e} (<= {max_abs:g}), worst row rel-L2 {rl:.3e} (<= {rel_l2:g})", flush=True)
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    excess = np.abs(got - want) - ulp_slack * np.abs(want)
+    ma = float(excess.max()) if excess.size else 0.0
+    _, rl = errors(got, want)
+    print(f"[parity] {what}: max-abs {ma:.3e} (<= {max_abs:g}{' beyond the bf16 spacing slack' if ulp_slack else ''}), "
+          f"worst row rel-L2 {rl:.3e} (<= {rel_l2:g})", flush=True)
     assert ma <= max_abs, f"{what}: max-abs {ma} > {max_abs}"
     assert rl <= rel_l2, f"{what}: row relative L2 {rl} > {rel_l2}"

@@ -1,0 +1,142 @@
+"""GPU parity for the rest of the layer (RMSNorm, linear + residual, SwiGLU) and the multi-layer
+partial prefill on the selected rows, against the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ct_oracle as O
+from paper_2605_24022_amd import binding as B
+from paper_2605_24022_amd import workloads as W
+from tests.gpu_util import assert_close, bits_of, dev_bf16, dev_i32, f64_of, pinned_bf16, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available()
+    B.load()
+    torch.cuda.set_device(0)
+
+
+def _bits(rng, shape, scale=1.0):
+    return W.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+@pytest.mark.parametrize("n,width", [(1, 512), (333, 4096), (130, 8192), (5, 64)])
+def test_rmsnorm(n, width):
+    rng = np.random.default_rng([31, n, width])
+    x = _bits(rng, (n, width), 3.0)
+    w = W.f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(width)).astype(np.float32))   # outputs stay below 8: bf16 spacing 2^-5
+    say(f"rmsnorm n={n} width={width}")
+    out = torch.zeros((n, width), dtype=torch.bfloat16, device="cuda")
+    B.ct_rmsnorm(dev_bf16(x), dev_bf16(w), 1e-5, n, width, out)
+    torch.cuda.synchronize()
+    assert_close(f64_of(out), O.rmsnorm(W.bf16_bits_to_f64(x), W.bf16_bits_to_f64(w), 1e-5), "rmsnorm", rel_l2=3e-3)
+
+
+@pytest.mark.parametrize("n,k_len,n_out,res", [(257, 512, 512, True), (100, 1024, 192, False), (300, 14336, 4096, True),
+                                                (64, 64, 64, True)])
+def test_linear_with_residual(n, k_len, n_out, res):
+    rng = np.random.default_rng([32, n, k_len, n_out])
+    x, w = _bits(rng, (n, k_len)), _bits(rng, (n_out, k_len), 1.0 / math.sqrt(k_len))
+    r = _bits(rng, (n, n_out)) if res else None
+    say(f"linear n={n} k={k_len} out={n_out} residual={res}")
+    out = torch.zeros((n, n_out), dtype=torch.bfloat16, device="cuda")
+    B.ct_linear(dev_bf16(x), n, k_len, dev_bf16(w), n_out, None if r is None else dev_bf16(r), out)
+    torch.cuda.synchronize()
+    want = W.bf16_bits_to_f64(x) @ W.bf16_bits_to_f64(w).T
+    if res:
+        want = want + W.bf16_bits_to_f64(r)
+    assert_close(f64_of(out), want, "linear")
+    if res:   # in place on the residual
+        rt = dev_bf16(r)
+        B.ct_linear(dev_bf16(x), n, k_len, dev_bf16(w), n_out, rt, rt)
+        torch.cuda.synchronize()
+        assert torch.equal(rt, out)
+
+
+@pytest.mark.parametrize("n,k_len,n_out", [(257, 512, 1408), (129, 4096, 14336), (7, 64, 64)])
+def test_swiglu(n, k_len, n_out):
+    rng = np.random.default_rng([33, n, k_len, n_out])
+    x = _bits(rng, (n, k_len))
+    wg, wu = _bits(rng, (n_out, k_len), 1.0 / math.sqrt(k_len)), _bits(rng, (n_out, k_len), 1.0 / math.sqrt(k_len))
+    say(f"swiglu n={n} k={k_len} out={n_out}")
+    out = torch.zeros((n, n_out), dtype=torch.bfloat16, device="cuda")
+    B.ct_swiglu(dev_bf16(x), n, k_len, dev_bf16(wg), dev_bf16(wu), n_out, out)
+    torch.cuda.synchronize()
+    xf = W.bf16_bits_to_f64(x)
+    want = O.silu(xf @ W.bf16_bits_to_f64(wg).T) * (xf @ W.bf16_bits_to_f64(wu).T)
+    assert_close(f64_of(out), want, "swiglu", ulp_slack=2.0 ** -8)   # products of two N(0,1) projections reach 16
+
+
+# ------------------------------------------------------------------------------ the stack
+def _layers_f64(sw):
+    return [{k: W.bf16_bits_to_f64(v) for k, v in lw.items()} for lw in sw.layers]
+
+
+def _run_stack(sw, hidden0_bits, layer_range=None, pinned=True):
+    sp, sh = sw.spec, sw.spec.shape
+    cfg = B.cfg_from_shape(sh)
+    n_ctx, n_sel = sp.n_ctx, sp.n_sel
+    lay = sw.layers if layer_range is None else sw.layers[layer_range[0]:layer_range[1]]
+    keep, entries = [], []
+    for lw in lay:
+        d = {k: dev_bf16(lw[k]) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")}
+        kc, vc = lw["k_cache"].copy(), lw["v_cache"].copy()
+        kc[sw.sel_idx] = 0x7FC0          # stale rows at the selected slots must never be read
+        vc[sw.sel_idx] = 0x7FC0
+        kp, vp = (pinned_bf16(kc), pinned_bf16(vc)) if pinned else (dev_bf16(kc), dev_bf16(vc))
+        ch = B.make_chunks([dict(k=kp[int(sw.chunk_rows[c]):int(sw.chunk_rows[c + 1])],
+                                 v=vp[int(sw.chunk_rows[c]):int(sw.chunk_rows[c + 1])],
+                                 n_tokens=int(sw.chunk_rows[c + 1] - sw.chunk_rows[c]), old_pos_start=0,
+                                 new_pos_start=int(sw.chunk_new_start[c]), location=1 if pinned else 0)
+                            for c in range(sp.n_chunks)])
+        keep.append((d, kp, vp, ch))
+        d["chunks"] = ch
+        entries.append(d)
+    layers = B.make_layers(entries)
+    ws_bytes = B.ct_stack_workspace_bytes(cfg, sw.ffn_dim, n_ctx, n_sel)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    k_bufs = torch.full((2, n_ctx, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v_bufs = torch.full_like(k_bufs, float("nan"))
+    h = dev_bf16(hidden0_bits).clone()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    say(f"stack {sp.name} layers={len(entries)} n_ctx={n_ctx} n_sel={n_sel} ffn={sw.ffn_dim} pinned={pinned}")
+    B.ct_partial_prefill_stack(cfg, sw.ffn_dim, sw.rms_eps, layers, len(entries), sp.n_chunks, h, dev_i32(sw.sel_idx),
+                               n_sel, sp.ratio_pct / 100.0, k_bufs, v_bufs, ws, ws_bytes, s1, s2)
+    torch.cuda.synchronize()
+    return h
+
+
+@pytest.mark.parametrize("pinned", [True, False])
+@pytest.mark.parametrize("ratio", [15, 100])
+def test_small_stack_end_to_end(pinned, ratio):
+    """4 layers, unforced: bf16 rounding compounds through the layers, so the bound is looser."""
+    sh = W.LayerShape(512, 8, 2, 64, 1.0e4)
+    sp = W.custom_spec(f"stack-small-r{ratio}", sh, 4, 512, ratio, seed=77)
+    sw = W.make_stack_workload(sp, n_layers=4, ffn_dim=1408)
+    h = _run_stack(sw, sw.hidden0, pinned=pinned)
+    f = _layers_f64(sw)
+    want = O.partial_prefill_stack(W.bf16_bits_to_f64(sw.hidden0), f, sw.old_pos, sw.new_pos, sw.sel_idx,
+                                   sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta, sw.rms_eps)
+    assert_close(f64_of(h), want, "4-layer stack output", max_abs=1e-1, rel_l2=2e-2, ulp_slack=2.0 ** -7)   # unforced: rounding compounds over 4 layers
+
+
+def test_llama_shaped_layers_teacher_forced():
+    """Llama-3-8B layer shape, 2 layers over an 8192-token context: each layer is checked on its own
+    with the oracle fed the GPU's input of that layer (teacher forcing)."""
+    sp = W.custom_spec("stack-llama-8k", W.LLAMA3_8B, 8, 1024, 15, seed=78)
+    sw = W.make_stack_workload(sp, n_layers=2, ffn_dim=14336)
+    sh = sp.shape
+    f = _layers_f64(sw)
+    h_in = sw.hidden0
+    for l in range(2):
+        h_out = _run_stack(sw, h_in, layer_range=(l, l + 1))
+        want, _, _ = O.transformer_layer(W.bf16_bits_to_f64(h_in), f[l], sw.old_pos, sw.new_pos, sw.sel_idx,
+                                         sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta, sw.rms_eps)
+        assert_close(f64_of(h_out), want, f"layer {l} output (teacher forced)", ulp_slack=2.0 ** -8)
+        h_in = bits_of(h_out)

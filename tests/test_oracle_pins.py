@@ -333,3 +333,86 @@ def test_empty_selection_is_full_reuse():
     assert out.shape == (0, 4, D)
     np.testing.assert_allclose(kf, O.rotate(k_cache, new - old, theta), atol=0)
     assert np.array_equal(vf, v_cache)
+
+
+# ------------------------------------------------------------------ rest of the layer, stack
+def test_rmsnorm_and_swiglu_against_library_and_closed_form():
+    x, w = _rand(7, 24), _rand(24)
+    want = F.rms_norm(torch.tensor(x), (24,), torch.tensor(w), eps=1e-5).numpy()
+    np.testing.assert_allclose(O.rmsnorm(x, w, 1e-5), want, atol=1e-12)
+    # a constant row c has mean square c^2: y = c / sqrt(c^2 + eps) * w
+    c = np.full((1, 24), 3.0)
+    np.testing.assert_allclose(O.rmsnorm(c, w, 0.25), 3.0 / math.sqrt(9.25) * w[None, :], atol=1e-14)
+    wg, wu, wd = _rand(10, 24), _rand(10, 24), _rand(24, 10)
+    xt = torch.tensor(x)
+    want = F.linear(F.silu(F.linear(xt, torch.tensor(wg))) * F.linear(xt, torch.tensor(wu)), torch.tensor(wd)).numpy()
+    np.testing.assert_allclose(O.swiglu_ffn(x, wg, wu, wd), want, atol=1e-11)
+    assert O.silu(np.array([0.0]))[0] == 0.0 and abs(O.silu(np.array([1.0]))[0] - 1 / (1 + math.exp(-1))) < 1e-15
+
+
+def _torch_block_stack(h0, layers, pos, Hq, Hkv, D, theta, eps):
+    """Ordinary full causal prefill of a pre-norm decoder stack with library routines only."""
+    h = torch.tensor(h0)
+    N, E = h.shape
+    w = torch.tensor(theta, dtype=torch.float64) ** (-torch.arange(0, D, 2, dtype=torch.float64) / D)
+    ang = torch.tensor(pos, dtype=torch.float64)[:, None] * w[None, :]
+    e = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+
+    def rope(t):
+        z = torch.complex(t[..., :D // 2], t[..., D // 2:]) * e
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    for lw in layers:
+        x = F.rms_norm(h, (E,), torch.tensor(lw["attn_norm"]), eps=eps)
+        y = F.linear(x, torch.tensor(lw["wqkv"]))
+        q, k, v = torch.split(y, [Hq * D, Hkv * D, Hkv * D], dim=1)
+        q, k, v = rope(q.reshape(N, Hq, D)), rope(k.reshape(N, Hkv, D)), v.reshape(N, Hkv, D)
+        a = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None], v.transpose(0, 1)[None],
+                                           is_causal=True, enable_gqa=True)[0].transpose(0, 1).reshape(N, Hq * D)
+        h = h + F.linear(a, torch.tensor(lw["wo"]))
+        x = F.rms_norm(h, (E,), torch.tensor(lw["ffn_norm"]), eps=eps)
+        h = h + F.linear(F.silu(F.linear(x, torch.tensor(lw["w_gate"]))) * F.linear(x, torch.tensor(lw["w_up"])),
+                         torch.tensor(lw["w_down"]))
+    return h.numpy()
+
+
+def _rand_layers(n_layers, N, E, Hq, Hkv, D, Fdim, with_cache=True):
+    layers = []
+    for _ in range(n_layers):
+        layers.append(dict(attn_norm=1 + 0.1 * _rand(E), wqkv=_rand((Hq + 2 * Hkv) * D, E) / math.sqrt(E),
+                           wo=_rand(E, Hq * D) / math.sqrt(Hq * D), ffn_norm=1 + 0.1 * _rand(E),
+                           w_gate=_rand(Fdim, E) / math.sqrt(E), w_up=_rand(Fdim, E) / math.sqrt(E),
+                           w_down=_rand(E, Fdim) / math.sqrt(Fdim),
+                           k_cache=_rand(N, Hkv, D) if with_cache else np.full((N, Hkv, D), np.nan),
+                           v_cache=_rand(N, Hkv, D) if with_cache else np.full((N, Hkv, D), np.nan)))
+    return layers
+
+
+def test_stack_at_ratio_100_equals_library_decoder_stack():
+    N, E, Hq, Hkv, D, Fdim, theta, eps = 24, 16, 4, 2, 8, 40, 1.0e4, 1e-5
+    layers = _rand_layers(3, N, E, Hq, Hkv, D, Fdim, with_cache=False)   # cache poisoned: all rows recomputed
+    h0 = _rand(N, E)
+    pos = np.arange(N)
+    got = O.partial_prefill_stack(h0, layers, np.zeros(N, dtype=int), pos, np.arange(N), Hq, Hkv, D, theta, eps)
+    want = _torch_block_stack(h0, layers, pos, Hq, Hkv, D, theta, eps)
+    np.testing.assert_allclose(got, want, atol=1e-9)
+
+
+def test_stack_partial_first_selected_row_is_a_closed_chain():
+    """Selected row 0 sits at buffer row 0: it attends to itself only, so every layer reduces to
+    h += Wo v;  h += FFN(norm(h)) for that row, whatever the cache holds."""
+    N, E, Hq, Hkv, D, Fdim, theta, eps = 16, 16, 4, 2, 8, 24, 1.0e4, 1e-5
+    layers = _rand_layers(2, N, E, Hq, Hkv, D, Fdim)
+    sel = np.array([0, 5, 11])
+    h0 = _rand(3, E)
+    old, new = np.arange(N) % 4, np.arange(N)
+    got, inputs = O.partial_prefill_stack(h0, layers, old, new, sel, Hq, Hkv, D, theta, eps, keep_inputs=True)
+    h = h0[0].copy()
+    for lw in layers:
+        x = O.rmsnorm(h[None], lw["attn_norm"], eps)[0]
+        v = (lw["wqkv"] @ x)[(Hq + Hkv) * D:].reshape(Hkv, D)          # position 0: RoPE is the identity
+        a = np.repeat(v, Hq // Hkv, axis=0).reshape(-1)                # softmax over one key is 1
+        h = h + lw["wo"] @ a
+        h = h + O.swiglu_ffn(O.rmsnorm(h[None], lw["ffn_norm"], eps), lw["w_gate"], lw["w_up"], lw["w_down"])[0]
+    np.testing.assert_allclose(got[0], h, atol=1e-10)
+    assert len(inputs) == 2 and np.array_equal(inputs[0], h0)
