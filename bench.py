@@ -76,12 +76,101 @@ def cpu_baseline(wl, sample_rows: int, O, W, np):
     }
 
 
+def bench_stack(args, B, W, np, torch) -> int:
+    """Config 5: Llama-3-8B-shaped stack (hidden 4096, FFN 14336, 32/8 heads) over a 32768-token
+    context; partial prefill at the given ratio with per-layer KV streamed from pinned host
+    memory, against full prefill (r = 100 %, same kernels, nothing copied) on the same GPU.
+    Weights and caches are random (torch generator, seed 1005) - created on the device because
+    14 GB of weights would take minutes to draw on the host."""
+    sp = W.spec(5, args.ratio)
+    sh = sp.shape
+    n_layers, ffn = args.layers, 14336
+    cfg = B.cfg_from_shape(sh)
+    g = torch.Generator(device="cuda").manual_seed(1005)
+    E, qd, Hkv, D, N = sh.hidden, sh.n_q_heads * sh.head_dim, sh.n_kv_heads, sh.head_dim, sp.n_ctx
+
+    def rnd(shape, scale):
+        return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
+
+    log(f"creating {n_layers} layers of weights and {n_layers} x 128 MiB of pinned-host KV")
+    ones = torch.ones(E, dtype=torch.bfloat16, device="cuda")
+    weights, pools = [], []
+    for _ in range(n_layers):
+        weights.append(dict(attn_norm=ones, wqkv=rnd((sh.qkv_width, E), E ** -0.5), wo=rnd((E, qd), qd ** -0.5),
+                            ffn_norm=ones, w_gate=rnd((ffn, E), E ** -0.5), w_up=rnd((ffn, E), E ** -0.5),
+                            w_down=rnd((E, ffn), ffn ** -0.5)))
+        kp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
+        vp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
+        kp.copy_(rnd((N, Hkv, D), 1.0))
+        vp.copy_(rnd((N, Hkv, D), 1.0))
+        pools.append((kp, vp))
+    torch.cuda.synchronize()
+
+    def run(ratio_pct, steps, warmup):
+        spr = W.spec(5, ratio_pct) if ratio_pct < 100 else W.custom_spec("cfg5-full", sh, sp.n_chunks, sp.chunk_len, 100, "all", 1005)
+        sel_np = W.select_indices(spr)
+        n_sel = sel_np.size
+        sel = torch.from_numpy(sel_np).cuda()
+        entries, keep = [], []
+        for lw, (kp, vp) in zip(weights, pools):
+            ch = B.make_chunks([dict(k=kp[c * sp.chunk_len:(c + 1) * sp.chunk_len], v=vp[c * sp.chunk_len:(c + 1) * sp.chunk_len],
+                                     n_tokens=sp.chunk_len, old_pos_start=0, new_pos_start=c * sp.chunk_len, location=1)
+                                for c in range(sp.n_chunks)])
+            keep.append(ch)
+            d = dict(lw)
+            d["chunks"] = ch
+            entries.append(d)
+        layers = B.make_layers(entries)
+        ws_bytes = B.ct_stack_workspace_bytes(cfg, ffn, N, n_sel)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        k_bufs = torch.zeros((2, N, Hkv, D), dtype=torch.bfloat16, device="cuda")
+        v_bufs = torch.zeros_like(k_bufs)
+        h0 = rnd((n_sel, E), 1.0)
+        h = torch.empty_like(h0)
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def step():
+            h.copy_(h0)
+            torch.cuda.current_stream().synchronize()
+            B.ct_partial_prefill_stack(cfg, ffn, 1e-5, layers, n_layers, sp.n_chunks, h, sel, n_sel, ratio_pct / 100.0,
+                                       k_bufs, v_bufs, ws, ws_bytes, s1, s2)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        assert torch.isfinite(h.float()).all()
+        return ms, n_sel
+
+    log(f"partial prefill r={sp.ratio_pct}%")
+    ms_part, n_sel = run(sp.ratio_pct, args.steps, args.warmup)
+    log("full prefill (r=100%)")
+    ms_full, _ = run(100, max(1, args.steps // 4), 1)
+    line = {
+        "metric": f"end-to-end partial prefill latency, {n_layers}-layer stack @{N // 1024}K ctx, r={sp.ratio_pct}% (vs full prefill)",
+        "value": ms_part, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_part, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": sp.name, "layers": n_layers, "n_ctx": N, "n_sel": n_sel, "ffn_dim": ffn,
+                   "kv_pool": "pinned host, streamed one layer ahead on a second stream"},
+        "extra": {"full_prefill_ms": ms_full, "speedup_vs_full_prefill": ms_full / ms_part,
+                  "ms_per_layer_partial": ms_part / n_layers, "ms_per_layer_full": ms_full / n_layers,
+                  "host_to_device_bytes_per_layer": 2 * N * Hkv * D * 2},
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3])
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5])
+    ap.add_argument("--layers", type=int, default=32, help="config 5 only: number of layers")
     ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=96)
@@ -90,6 +179,8 @@ def main() -> int:
     ap.add_argument("--no-profile-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 4 if args.config == 5 else 50
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -106,6 +197,9 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     B.load()
+
+    if args.config == 5:
+        return bench_stack(args, B, W, np, torch)
 
     sp = W.spec(args.config, args.ratio)
     sh = sp.shape

@@ -146,3 +146,69 @@ def test_workspace_size_covers_staging_and_partials():
     staging = 1638 * (32 + 16) * 128 * 2
     assert B.ct_workspace_bytes(c, 32768, 1638) > staging + 26 * 8 * 2 * 256 * 128 * 4 - 1
     assert B.ct_workspace_bytes(c, 0, 0) == 0 and B.ct_workspace_bytes(c, 100, 200) == 0
+
+
+def test_norm_and_gemm_validation():
+    assert _status(B.ct_rmsnorm, None, FAKE, 1e-5, 4, 512, FAKE) == B.CT_ERR_NULL
+    assert _status(B.ct_rmsnorm, FAKE, FAKE, 1e-5, 4, 100, FAKE) == B.CT_ERR_UNSUPPORTED
+    assert _status(B.ct_rmsnorm, FAKE, FAKE, -1.0, 4, 512, FAKE) == B.CT_ERR_SHAPE
+    assert _status(B.ct_rmsnorm, FAKE, FAKE, 1e-5, -4, 512, FAKE) == B.CT_ERR_SHAPE
+    assert _status(B.ct_linear, FAKE, 4, 512, None, 512, None, FAKE) == B.CT_ERR_NULL
+    assert _status(B.ct_linear, FAKE, 4, 500, FAKE, 512, None, FAKE) == B.CT_ERR_UNSUPPORTED
+    assert _status(B.ct_linear, FAKE, 4, 512, FAKE, 100, None, FAKE) == B.CT_ERR_UNSUPPORTED
+    assert _status(B.ct_linear, FAKE, 4, 0, FAKE, 512, None, FAKE) == B.CT_ERR_SHAPE
+    assert _status(B.ct_linear, FAKE, 1 << 20, 4096, FAKE, 4096, None, FAKE) == B.CT_ERR_UNSUPPORTED   # > 4 GiB
+    assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, None, 512, FAKE) == B.CT_ERR_NULL
+    assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, FAKE, 96, FAKE) == B.CT_ERR_UNSUPPORTED
+    # empty work is legal and needs no GPU
+    B.ct_rmsnorm(None, None, 1e-5, 0, 512, None)
+    B.ct_linear(None, 0, 512, None, 512, None, None)
+    B.ct_swiglu(None, 0, 512, None, None, 512, None)
+
+
+def _layers(n_layers=2, n_chunks=4, length=256, **kw):
+    entries = []
+    for _ in range(n_layers):
+        entries.append(dict(attn_norm=FAKE, wqkv=FAKE, wo=FAKE, ffn_norm=FAKE, w_gate=FAKE, w_up=FAKE, w_down=FAKE,
+                            chunks=_chunks(n_chunks, length, **kw)))
+    return entries
+
+
+def test_stack_validation():
+    assert ctypes.sizeof(B.LayerWeights) == 64
+    c = B.make_cfg(512, 8, 2, 64, 1e4)
+    need = B.ct_stack_workspace_bytes(c, 1536, 1024, 153)
+    assert need > B.ct_workspace_bytes(c, 1024, 153) and need % 256 == 0
+    assert B.ct_stack_workspace_bytes(c, 0, 1024, 153) == 0
+    assert B.ct_stack_workspace_bytes(c, 1536, 100, 200) == 0
+
+    def call(entries=None, n_layers=2, n_chunks=4, ffn=1536, eps=1e-5, hidden=FAKE, sel=FAKE, n_sel=153, ratio=0.15,
+             kb=FAKE, vb=FAKE, ws=FAKE + 0xF0, ws_bytes=need, s1=None, s2=None):
+        layers = B.make_layers(entries if entries is not None else _layers())
+        return _status(B.ct_partial_prefill_stack, c, ffn, eps, layers, n_layers, n_chunks, hidden, sel, n_sel, ratio,
+                       kb, vb, ws, ws_bytes, s1, s2)
+
+    assert FAKE + 0xF0 & 255 != 0
+    assert call() == B.CT_ERR_WORKSPACE                       # everything fine up to the misaligned workspace
+    assert call(ws=None) == B.CT_ERR_WORKSPACE
+    assert call(ws=FAKE, ws_bytes=need - 1) == B.CT_ERR_WORKSPACE
+    assert call(n_layers=0) == B.CT_ERR_SHAPE
+    assert call(n_chunks=0) == B.CT_ERR_SHAPE
+    assert call(n_chunks=65) == B.CT_ERR_UNSUPPORTED
+    assert call(ffn=1000) == B.CT_ERR_UNSUPPORTED
+    assert call(eps=-1.0) == B.CT_ERR_SHAPE
+    assert call(n_sel=0, ratio=-1.0) == B.CT_ERR_SHAPE
+    assert call(n_sel=2000, ratio=-1.0) == B.CT_ERR_SHAPE
+    assert call(n_sel=150) == B.CT_ERR_RATIO
+    assert call(hidden=None) == B.CT_ERR_NULL
+    assert call(kb=None) == B.CT_ERR_NULL
+    bad = _layers(); bad[1]["wo"] = None
+    assert call(entries=bad) == B.CT_ERR_NULL
+    bad = _layers(); bad[1]["chunks"][2].n_tokens = 128      # geometry differs between layers
+    assert call(entries=bad) == B.CT_ERR_SHAPE
+    bad = _layers(); bad[0]["chunks"][2].new_pos_start = 100
+    assert call(entries=bad) == B.CT_ERR_SHAPE
+    bad = _layers(); bad[1]["chunks"][3].v = None
+    assert call(entries=bad) == B.CT_ERR_NULL
+    # pinned-host chunks need a second stream (both default here)
+    assert call(entries=_layers(location=1), ws=FAKE) == B.CT_ERR_SHAPE
