@@ -76,6 +76,66 @@ def cpu_baseline(wl, sample_rows: int, O, W, np):
     }
 
 
+def cold_cache_bandwidth(B, cfg, wl, sp, torch, np, reps: int = 3):
+    """Stand-alone bandwidth kernels under a cold-cache protocol: every launch works on a
+    different buffer out of a ring of >= 1 GiB, so nothing it reads is left in the last-level
+    cache by the launch before.  In-place re-RoPE of all N key rows (credited with the N - n rows
+    that have to be rotated), scatter of the n recomputed rows, and a plain device copy of the
+    same size as the re-RoPE traffic for the ceiling.  Durations come from the library's HIP
+    events on the launch stream."""
+    sh = sp.shape
+    N, n = sp.n_ctx, sp.n_sel
+    row = sh.n_kv_heads * sh.head_dim
+    ring = max(2, (1 << 30) // (N * row * 2))
+    kb = [torch.randn((N, sh.n_kv_heads, sh.head_dim), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+          for _ in range(ring)]
+    vb = [torch.zeros_like(kb[0]) for _ in range(ring)]
+    old = torch.from_numpy(wl.old_pos).cuda()
+    new = torch.from_numpy(wl.new_pos).cuda()
+    sel = torch.from_numpy(wl.sel_idx).cuda()
+    ks = torch.randn((n, sh.n_kv_heads, sh.head_dim), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    vs = torch.randn_like(ks)
+    st = torch.cuda.current_stream()
+    res = {"ring_buffers": ring, "ring_bytes": ring * N * row * 2 * 2}
+
+    def timed(name, fn):
+        fn(0)
+        torch.cuda.synchronize()
+        B.ct_profile_reset()
+        B.ct_set_profiling(True)
+        for r in range(reps):
+            for i in range(ring):
+                fn(i)
+        torch.cuda.synchronize()
+        B.ct_set_profiling(False)
+        cnt, ms = B.ct_profile_read(name)
+        B.ct_profile_reset()
+        return ms / cnt * 1e-3
+
+    t = timed("rerope", lambda i: B.ct_rerope_keys(cfg, kb[i], kb[i], old, new, N, st))
+    credited = 2.0 * (N - n) * row * 2 + 8.0 * (N - n)
+    moved = 2.0 * N * row * 2 + 8.0 * N
+    res["rerope_in_place"] = {"avg_us": t * 1e6, "gbs_credited": credited / t / 1e9, "gbs_moved": moved / t / 1e9,
+                              "frac_of_hbm_peak_credited": credited / t / 1e9 / PEAK_HBM_GBS,
+                              "frac_of_hbm_peak_moved": moved / t / 1e9 / PEAK_HBM_GBS}
+    t = timed("scatter", lambda i: B.ct_scatter_kv(cfg, kb[i], vb[i], N, ks, vs, sel, n, st))
+    sb = 2.0 * 2.0 * n * row * 2 + 4.0 * n
+    res["scatter"] = {"avg_us": t * 1e6, "gbs": sb / t / 1e9, "frac_of_hbm_peak": sb / t / 1e9 / PEAK_HBM_GBS}
+    # ceiling: plain device copy K ring -> V ring, same bytes as the in-place rotation moves
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    vb[0].copy_(kb[0])
+    torch.cuda.synchronize()
+    e0.record()
+    for r in range(reps):
+        for i in range(ring):
+            vb[i].copy_(kb[(i + ring // 2) % ring])
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / (reps * ring)
+    res["plain_copy"] = {"avg_us": t * 1e6, "gbs": 2.0 * N * row * 2 / t / 1e9}
+    return res
+
+
 def bench_stack(args, B, W, np, torch) -> int:
     """Config 5: Llama-3-8B-shaped stack (hidden 4096, FFN 14336, 32/8 heads) over a 32768-token
     context; partial prefill at the given ratio with per-layer KV streamed from pinned host
@@ -176,6 +236,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=96)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one plain 512 MiB device copy before the timed region (reference for HBM byte counters)")
+    ap.add_argument("--no-cold-cache", action="store_true",
+                    help="skip the stand-alone re-RoPE / scatter bandwidth runs (outside the timed region)")
     ap.add_argument("--no-profile-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
     args = ap.parse_args()
@@ -293,6 +355,9 @@ def main() -> int:
         extra["rerope_plus_vcopy_gbs_moved"] = moved / (kern["rerope"]["ms_per_step"] * 1e-3) / 1e9
     if "scatter" in kern:
         extra["scatter_gbs"] = scatter_bytes / (kern["scatter"]["ms_per_step"] * 1e-3) / 1e9
+
+    if not args.no_cold_cache:
+        extra["cold_cache"] = cold_cache_bandwidth(B, cfg, wl, sp, torch, np)
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -169,7 +169,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // tiles that are never consumed.
   auto issue_one = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr, int idx) __attribute__((always_inline)) {
     const int key = min(k0 + ld_row + NWAVES * RPI * idx, a.n_ctx - 1);
-    dma16(base, (uint32_t)key * kv_row_bytes + lane_off, stage_addr + (NWAVES * idx + wave) * 1024);
+    dma16(base, __umul24(key, kv_row_bytes) + lane_off, stage_addr + (NWAVES * idx + wave) * 1024);
   };
   auto issue_rows = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr) __attribute__((always_inline)) {
 #pragma unroll
@@ -204,6 +204,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   float l_run = 0.f;   // per-lane partial row sum; lanes l and l^32 are added at the end
   f32x16 s[2];         // S^T of the tile whose scores were computed last (two 32-key sub-tiles)
   bf16x8 pf[2][2];     // P^T fragments (sub-tile u, 16-key step t) of the tile whose softmax was done last
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[u][t][e] = (__bf16)0.0f;
 
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   auto load_vfrag = [&](const unsigned char* vrow, int m) __attribute__((always_inline)) -> bf16x8 {
@@ -214,47 +220,44 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
 
   // ---- M part: O^T += V^T P^T (previous tile), S^T = K Q^T (this tile) ----------------------------
-  // The wave runs it at raised priority: its instruction stream is sparse (MFMAs, fragment
-  // reads, the look-ahead loads) and must not queue behind the dense softmax stream of the
-  // other wave on the SIMD.  The look-ahead loads are left to the softmax wave.
-  auto part_m = [&](bool do_pv, const unsigned char* vb, bool do_qk, const unsigned char* kb) __attribute__((always_inline)) {
+  // One stream of NPV + NQK (fragment read, MFMA) steps.  A step needs one A fragment from LDS;
+  // with one wave per SIMD in this part nothing else hides the LDS latency, so the reads run PD
+  // fragments (PD * 32 MFMA cycles) ahead of their MFMAs through a ring of PD + 1 fragment
+  // registers, across the PV -> QK boundary as well.
+  // The wave runs it at raised priority: its instruction stream is sparse and must not queue
+  // behind the dense softmax stream of the other wave on the SIMD.
+  // The first period has no previous tile and the last one no next tile; both still run the
+  // whole stream (P^T = 0 in the first, S^T unused in the last, the stages hold loaded data).
+  constexpr int NPV = 4 * MT, NQK = 2 * KS;
+#ifndef CT_ATTN_PD
+#define CT_ATTN_PD 7
+#endif
+  constexpr int PD = CT_ATTN_PD;
+  auto load_frag = [&](int j, const unsigned char* vb, const unsigned char* kb) __attribute__((always_inline)) -> bf16x8 {
+    if (j < NPV) return load_vfrag(vb + 16 * (j / MT) * ROWB, j % MT);
+    const int ks = (j - NPV) >> 1, u = (j - NPV) & 1;
+    return *reinterpret_cast<const bf16x8*>(kb + k_off[ks] + u * 32 * ROWB);
+  };
+  auto part_m = [&](const unsigned char* vb, const unsigned char* kb) __attribute__((always_inline)) {
     __builtin_amdgcn_s_setprio(3);
-    if (do_pv) {
-      bf16x8 vf[2][MT];
+    bf16x8 fr[PD + 1];
 #pragma unroll
-      for (int m = 0; m < MT; ++m) vf[0][m] = load_vfrag(vb, m);
+    for (int j = 0; j < PD; ++j) fr[j] = load_frag(j, vb, kb);
 #pragma unroll
-      for (int gi = 0; gi < 4; ++gi) {      // group gi = (sub-tile u, step t)
-        if (gi + 1 < 4) {
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-          for (int m = 0; m < MT; ++m) vf[(gi + 1) & 1][m] = load_vfrag(vb + 16 * (gi + 1) * ROWB, m);
-        }
+      for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
-          o[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[gi & 1][m], pf[gi >> 1][gi & 1], o[m], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);   // keep the fragment look-ahead at one group (register budget)
+    for (int j = 0; j < NPV + NQK; ++j) {
+      if (j + PD < NPV + NQK) fr[(j + PD) % (PD + 1)] = load_frag(j + PD, vb, kb);
+      if (j < NPV) {
+        const int gi = j / MT, m = j % MT;
+        o[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % (PD + 1)], pf[gi >> 1][gi & 1], o[m], 0, 0, 0);
+      } else {
+        const int ks = (j - NPV) >> 1, u = (j - NPV) & 1;
+        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % (PD + 1)], qf[ks], s[u], 0, 0, 0);
       }
-    }
-    if (do_qk) {
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
-      bf16x8 kf[2][2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) kf[0][u] = *reinterpret_cast<const bf16x8*>(kb + k_off[0] + u * 32 * ROWB);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) {
-#pragma unroll
-          for (int u = 0; u < 2; ++u)
-            kf[(ks + 1) & 1][u] = *reinterpret_cast<const bf16x8*>(kb + k_off[ks + 1] + u * 32 * ROWB);
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][u], qf[ks], s[u], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the read-ahead distance as written
     }
     __builtin_amdgcn_s_setprio(0);
   };
@@ -343,7 +346,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (!group_b) {
     for (int i = 0; i <= n_kt; ++i) {
       const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
-      part_m(i >= 1, v_lds + st_im1 * TILE_BYTES, i < n_kt, k_lds + st_i * TILE_BYTES);
+      part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES);
       __syncthreads();
       refill(i, st_im1, st_ip1);
       if (i < n_kt) part_v(k_lo + i * BN);
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       refill(i, st_im1, st_ip1);
       if (i >= 1) part_v(k_lo + (i - 1) * BN);
       __syncthreads();
-      part_m(i >= 1, v_lds + st_im1 * TILE_BYTES, i < n_kt, k_lds + st_i * TILE_BYTES);
+      part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES);
       end_of_period();
       st_im1 = st_i;
       st_i = st_ip1;
@@ -367,7 +370,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   // ---- epilogue -------------------------------------------------------------------------------
   const float l_tot = sum_with_lane_xor32(l_run);
-  if (a.n_splits == 1) {
+  if (kmax <= a.split_keys) {   // the tile's whole key range was this item: final result
     if (valid) {
       const float inv = 1.0f / l_tot;
       uint16_t* op = a.out + ((size_t)tokv * a.Hq + hq) * D + 4 * hi;
@@ -418,6 +421,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
   const int last_tok = min(tile * a.TM + a.TM, a.n_sel) - 1;
   const int kmax = a.sel_idx[last_tok] + 1;
   const int ns = min(a.n_splits, (kmax + a.split_keys - 1) / a.split_keys);
+  if (ns == 1) return;                             // written by the attention kernel itself
   const size_t item0 = ((size_t)tile * a.Hkv + g) * a.n_splits;
   const int C = a.cols;
   const size_t istride = (size_t)C * (D + 2);
