@@ -18,8 +18,9 @@
 //
 // Workgroup: 512 threads = 8 waves (2 feature halves x 4 token quarters), tile 256 features x
 // 256 tokens x 64 (K step), wave tile 128 x 64 = 4 x 2 MFMA tiles of
-// v_mfma_f32_32x32x16_bf16, two LDS stages of 64 KiB, one barrier per K step.  Two waves
-// share a SIMD, so one wave's fragment reads and waits hide behind the other's MFMAs.
+// v_mfma_f32_32x32x16_bf16, three weight-tile and two token-tile LDS slots of 32 KiB (loads run
+// two and one K steps ahead), one barrier per K step.  Two waves share a SIMD, so one wave's
+// waits hide behind the other's MFMAs.
 // Workgroups are numbered so that the ones resident on one XCD (ids congruent mod 8) cover a
 // patch of neighbouring tiles and share their W and X tiles in that XCD's L2.
 #include <string.h>
@@ -36,7 +37,7 @@ constexpr int BK = 64;            // reduction elements per stage
 constexpr int ROWB = BK * 2;      // LDS row in bytes (unpadded, swizzled)
 constexpr int A_BYTES = BF * ROWB;
 constexpr int B_BYTES = BT * ROWB;
-constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int A_SLOTS = 3, B_SLOTS = 2;   // LDS slots per operand tile
 constexpr int NWAVES = 8;
 constexpr int A_LOADS = BF / 8 / NWAVES;   // wave-wide loads (8 rows each) per wave and stage
 constexpr int B_LOADS = BT / 8 / NWAVES;
@@ -79,7 +80,7 @@ __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 template <int EPI, int D, int STYLE>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_kernel(GemmArgs a, RopeTable rope,
                                                                                              ChunkTable chunks) {
-  __shared__ __align__(1024) unsigned char lds[2 * STAGE_BYTES];
+  __shared__ __align__(1024) unsigned char lds[A_SLOTS * A_BYTES + B_SLOTS * B_BYTES];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
@@ -126,19 +127,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(base) : "memory");
   };
-  auto issue_stage = [&](int k0, int stage) __attribute__((always_inline)) {
+  // A (weight) tiles cycle through three LDS slots, B (token) tiles through two.  `half` selects
+  // the first or second half of a tile's loads.
+  auto issue_a = [&](int k0, int slot, int half) __attribute__((always_inline)) {
     const uint16_t* wk = a.wqkv + k0;      // scalar bases advanced to the K step
     const uint16_t* uk = EPI == EPI_SWIGLU ? a.w_up + k0 : wk;
-    const uint16_t* xk = a.hidden + k0;
-    const uint32_t st = lds_addr0 + stage * STAGE_BYTES;
+    const uint32_t st = lds_addr0 + slot * A_BYTES;
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
+    for (int j = half * (A_LOADS / 2); j < (half + 1) * (A_LOADS / 2); ++j) {
       // a wave-wide load covers 8 consecutive tile rows: all gate or all up
       const bool up = EPI == EPI_SWIGLU && ((((NWAVES * j + wave) * 8) >> 6) & 1);
       dma16(up ? uk : wk, a_off[j], st + (NWAVES * j + wave) * 1024);
     }
+  };
+  auto issue_b = [&](int k0, int slot, int half) __attribute__((always_inline)) {
+    const uint16_t* xk = a.hidden + k0;
+    const uint32_t st = lds_addr0 + A_SLOTS * A_BYTES + slot * B_BYTES;
 #pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) dma16(xk, b_off[j], st + A_BYTES + (NWAVES * j + wave) * 1024);
+    for (int j = half * (B_LOADS / 2); j < (half + 1) * (B_LOADS / 2); ++j)
+      dma16(xk, b_off[j], st + (NWAVES * j + wave) * 1024);
   };
 
   const int wf = wave & 1, wt = wave >> 1;
@@ -147,7 +154,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
   for (int ks = 0; ks < BK / 16; ++ks) {
     a_frag[ks] = (wf * 128 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
-    b_frag[ks] = A_BYTES + (wt * 64 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+    b_frag[ks] = (wt * 64 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
   }
 
   f32x16 acc[4][2];
@@ -158,29 +165,56 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
 
+  // Pipeline.  The weight tile of K step kt + 2 and the token tile of step kt + 1 are in flight
+  // while step kt is multiplied (all 160 KiB of LDS: 3 + 2 slots of 32 KiB); with one step in
+  // flight the load path alone (issue, L2 latency, barrier) takes as long as the MFMAs of a step.
+  // Loads are issued in the order B(kt + 1), A(kt + 2), so at the top of step kt everything but
+  // the newest A_LOADS loads - A(kt + 1) - is waited for.  Past the end the last step is loaded
+  // again into the free slots, which keeps the number of loads in flight, and the wait, uniform.
   const int nk = a.E / BK;
+  constexpr int WAIT_STEP = (A_LOADS & 15) | 0x0f70;   // s_waitcnt vmcnt(A_LOADS)
   __builtin_amdgcn_s_waitcnt(0x0f70);   // ordinary loads so far (row indices) are complete
-  issue_stage(0, 0);
+  issue_a(0, 0, 0); issue_a(0, 0, 1);
+  issue_b(0, 0, 0); issue_b(0, 0, 1);
+  issue_a(min(1, nk - 1) * BK, 1, 0); issue_a(min(1, nk - 1) * BK, 1, 1);
+  int sa = 0, sb = 0;
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's part of stage kt has landed
-    __syncthreads();                      // everybody's has; everybody is done reading the other stage
-    if (kt + 1 < nk) issue_stage((kt + 1) * BK, buf ^ 1);
-    const unsigned char* base = lds + buf * STAGE_BYTES;
+    __builtin_amdgcn_s_waitcnt(WAIT_STEP);   // this wave's loads of step kt have landed
+    __syncthreads();                         // everybody's have; everybody is done with step kt - 1
+    const unsigned char* a_base = lds + sa * A_BYTES;
+    const unsigned char* b_base = lds + A_SLOTS * A_BYTES + sb * B_BYTES;
+    const int sa_free = sa == 0 ? A_SLOTS - 1 : sa - 1;   // slot of step kt - 1
+    const int sb_free = sb ^ 1;
+    const int kb1 = min(kt + 1, nk - 1) * BK, ka2 = min(kt + 2, nk - 1) * BK;
+    // The fragment reads of MFMA group ks + 1 are issued before the MFMAs of group ks (two
+    // register sets), so a wave waits for LDS once per K step instead of once per group.
+    bf16x8 fa[2][4], fb[2][2];
+    auto read_frags = [&](int ks, int set) __attribute__((always_inline)) {
+#pragma unroll
+      for (int n = 0; n < 2; ++n) fb[set][n] = *reinterpret_cast<const bf16x8*>(b_base + b_frag[ks] + n * 32 * ROWB);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) fa[set][m] = *reinterpret_cast<const bf16x8*>(a_base + a_frag[ks] + m * 32 * ROWB);
+    };
+    read_frags(0, 0);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[4], fb[2];
-#pragma unroll
-      for (int m = 0; m < 4; ++m) fa[m] = *reinterpret_cast<const bf16x8*>(base + a_frag[ks] + m * 32 * ROWB);
-#pragma unroll
-      for (int n = 0; n < 2; ++n) fb[n] = *reinterpret_cast<const bf16x8*>(base + b_frag[ks] + n * 32 * ROWB);
+      // the loads go out a quarter at a time, one quarter per MFMA group: a burst of all of them
+      // from all eight waves would queue at the texture addresser
+      if (ks < 2) issue_b(kb1, sb_free, ks);
+      else issue_a(ka2, sa_free, ks - 2);
+      if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int m = 0; m < 4; ++m)
 #pragma unroll
         for (int n = 0; n < 2; ++n)
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][m], fb[ks & 1][n], acc[m][n], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    sa = sa == A_SLOTS - 1 ? 0 : sa + 1;
+    sb = sb_free;
   }
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // the repeated loads of the last steps have landed before the LDS is released
 
   // ---- epilogues ---------------------------------------------------------------------------------
   // accumulator element i of tile (m, n): row f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
