@@ -32,15 +32,14 @@ namespace ct {
 namespace {
 
 constexpr int BF = 256;           // features per workgroup
-constexpr int BT = 256;           // tokens per workgroup
+// tokens per workgroup: 128 * NB, NB = MFMA column tiles per wave (template parameter; 2 unless the
+// grid would otherwise end in a mostly empty last round of workgroups)
 constexpr int BK = 64;            // reduction elements per stage
 constexpr int ROWB = BK * 2;      // LDS row in bytes (unpadded, swizzled)
 constexpr int A_BYTES = BF * ROWB;
-constexpr int B_BYTES = BT * ROWB;
 constexpr int A_SLOTS = 3, B_SLOTS = 2;   // LDS slots per operand tile
 constexpr int NWAVES = 8;
 constexpr int A_LOADS = BF / 8 / NWAVES;   // wave-wide loads (8 rows each) per wave and stage
-constexpr int B_LOADS = BT / 8 / NWAVES;
 
 enum Epilogue { EPI_QKV_ROPE = 0, EPI_LINEAR = 1, EPI_SWIGLU = 2 };
 
@@ -77,9 +76,12 @@ __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 // EPI_SWIGLU: the 128 A rows of a wave are 64 gate rows followed by the 64 up rows of the same
 // output features, so gate and up of one (feature, token) land in the same lane and register
 // index of accumulator tiles (m, m + 2) - the same pairing the half-split RoPE uses.
-template <int EPI, int D, int STYLE>
+template <int EPI, int D, int STYLE, int NB>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_kernel(GemmArgs a, RopeTable rope,
                                                                                              ChunkTable chunks) {
+  constexpr int BT = 128 * NB;
+  constexpr int B_BYTES = BT * ROWB;
+  constexpr int B_LOADS = BT / 8 / NWAVES;
   __shared__ __align__(1024) unsigned char lds[A_SLOTS * A_BYTES + B_SLOTS * B_BYTES];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -154,14 +156,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
   for (int ks = 0; ks < BK / 16; ++ks) {
     a_frag[ks] = (wf * 128 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
-    b_frag[ks] = (wt * 64 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+    b_frag[ks] = (wt * 32 * NB + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
   }
 
-  f32x16 acc[4][2];
+  f32x16 acc[4][NB];
 #pragma unroll
   for (int m = 0; m < 4; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
+    for (int n = 0; n < NB; ++n)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
 
@@ -188,10 +190,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int kb1 = min(kt + 1, nk - 1) * BK, ka2 = min(kt + 2, nk - 1) * BK;
     // The fragment reads of MFMA group ks + 1 are issued before the MFMAs of group ks (two
     // register sets), so a wave waits for LDS once per K step instead of once per group.
-    bf16x8 fa[2][4], fb[2][2];
+    bf16x8 fa[2][4], fb[2][NB];
     auto read_frags = [&](int ks, int set) __attribute__((always_inline)) {
 #pragma unroll
-      for (int n = 0; n < 2; ++n) fb[set][n] = *reinterpret_cast<const bf16x8*>(b_base + b_frag[ks] + n * 32 * ROWB);
+      for (int n = 0; n < NB; ++n) fb[set][n] = *reinterpret_cast<const bf16x8*>(b_base + b_frag[ks] + n * 32 * ROWB);
 #pragma unroll
       for (int m = 0; m < 4; ++m) fa[set][m] = *reinterpret_cast<const bf16x8*>(a_base + a_frag[ks] + m * 32 * ROWB);
     };
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int n = 0; n < 2; ++n)
+        for (int n = 0; n < NB; ++n)
           acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][m], fb[ks & 1][n], acc[m][n], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -221,8 +223,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if constexpr (EPI == EPI_LINEAR) {
     const int f0 = f_blk + wf * 128;
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int t = t_blk + wt * 64 + n * 32 + l32;
+    for (int n = 0; n < NB; ++n) {
+      const int t = t_blk + wt * 32 * NB + n * 32 + l32;
       if (t >= a.n_sel) continue;
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
@@ -247,8 +249,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   } else if constexpr (EPI == EPI_SWIGLU) {
     const int f0 = f_blk + wf * 64;          // output features of this wave: f0 .. f0 + 63
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int t = t_blk + wt * 64 + n * 32 + l32;
+    for (int n = 0; n < NB; ++n) {
+      const int t = t_blk + wt * 32 * NB + n * 32 + l32;
       if (t >= a.n_sel) continue;
 #pragma unroll
       for (int m = 0; m < 2; ++m) {          // gate tile m, up tile m + 2
@@ -277,8 +279,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int rope_end = (a.Hq + a.Hkv) * D;   // features below this are q or k heads
     const int q_end = a.Hq * D;
   #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int t = t_blk + wt * 64 + n * 32 + l32;
+    for (int n = 0; n < NB; ++n) {
+      const int t = t_blk + wt * 32 * NB + n * 32 + l32;
       const bool t_ok = t < a.n_sel;
       const int tc = t_ok ? t : a.n_sel - 1;
       const int32_t pos = a.sel_pos ? a.sel_pos[tc] : position_of_row(chunks, a.sel_idx[tc]);
@@ -354,9 +356,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 }  // namespace
 
-static void fill_tiles(GemmArgs* a, bool swiglu) {
+static void fill_tiles(GemmArgs* a, bool swiglu, int nb) {
   a->nF = (a->O + (swiglu ? BF / 2 : BF) - 1) / (swiglu ? BF / 2 : BF);
-  a->nT = (a->n_sel + BT - 1) / BT;
+  a->nT = (a->n_sel + 128 * nb - 1) / (128 * nb);
+}
+
+// Token tile width for a launch: 256 tokens per workgroup unless the workgroups then fill the last
+// round over the 256 compute units so badly that 128-token tiles (about 0.56 of the time of a
+// 256-token tile each) finish earlier.
+static int pick_nb(const GemmArgs& a, bool swiglu) {
+  GemmArgs t = a;
+  double cost[3] = {0, 0, 0};
+  for (int nb = 1; nb <= 2; ++nb) {
+    fill_tiles(&t, swiglu, nb);
+    const long wgs = (long)t.nF * t.nT;
+    cost[nb] = (double)((wgs + 255) / 256) * (nb == 2 ? 1.0 : 0.56);
+  }
+  return cost[1] < cost[2] ? 1 : 2;
 }
 
 template <typename Kernel>
@@ -393,7 +409,7 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
   a.Hq = cfg->n_q_heads;
   a.Hkv = cfg->n_kv_heads;
   a.O = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
-  fill_tiles(&a, false);
+  fill_tiles(&a, false, 2);
   RopeTable rope;
   fill_rope_table(cfg, &rope);
   ChunkTable tab;
@@ -406,10 +422,10 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
     tab.new_start[0] = 0;
   }
   if (cfg->head_dim == 128)
-    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0>, a, rope, tab, KC_QKV, s)
-                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1>, a, rope, tab, KC_QKV, s);
-  return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0>, a, rope, tab, KC_QKV, s)
-                              : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1>, a, rope, tab, KC_QKV, s);
+    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0, 2>, a, rope, tab, KC_QKV, s)
+                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1, 2>, a, rope, tab, KC_QKV, s);
+  return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0, 2>, a, rope, tab, KC_QKV, s)
+                              : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1, 2>, a, rope, tab, KC_QKV, s);
 }
 
 ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
@@ -424,12 +440,14 @@ ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void*
   a.n_sel = n_tok;
   a.E = k_len;
   a.O = n_out;
-  fill_tiles(&a, false);
+  const int nb = pick_nb(a, false);
+  fill_tiles(&a, false, nb);
   RopeTable rope;
   memset(&rope, 0, sizeof(rope));
   ChunkTable tab;
   memset(&tab, 0, sizeof(tab));
-  return launch_gemm(gemm_kernel<EPI_LINEAR, 128, 0>, a, rope, tab, KC_LINEAR, s);
+  return nb == 2 ? launch_gemm(gemm_kernel<EPI_LINEAR, 128, 0, 2>, a, rope, tab, KC_LINEAR, s)
+                 : launch_gemm(gemm_kernel<EPI_LINEAR, 128, 0, 1>, a, rope, tab, KC_LINEAR, s);
 }
 
 ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
@@ -444,12 +462,14 @@ ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void*
   a.n_sel = n_tok;
   a.E = k_len;
   a.O = n_out;
-  fill_tiles(&a, true);
+  const int nb = pick_nb(a, true);
+  fill_tiles(&a, true, nb);
   RopeTable rope;
   memset(&rope, 0, sizeof(rope));
   ChunkTable tab;
   memset(&tab, 0, sizeof(tab));
-  return launch_gemm(gemm_kernel<EPI_SWIGLU, 128, 0>, a, rope, tab, KC_LINEAR, s);
+  return nb == 2 ? launch_gemm(gemm_kernel<EPI_SWIGLU, 128, 0, 2>, a, rope, tab, KC_LINEAR, s)
+                 : launch_gemm(gemm_kernel<EPI_SWIGLU, 128, 0, 1>, a, rope, tab, KC_LINEAR, s);
 }
 
 }  // namespace ct
