@@ -159,10 +159,13 @@ def bench_stack(args, B, W, np, torch) -> int:
         weights.append(dict(attn_norm=ones, wqkv=rnd((sh.qkv_width, E), E ** -0.5), wo=rnd((E, qd), qd ** -0.5),
                             ffn_norm=ones, w_gate=rnd((ffn, E), E ** -0.5), w_up=rnd((ffn, E), E ** -0.5),
                             w_down=rnd((E, ffn), ffn ** -0.5)))
-        kp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
-        vp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
-        kp.copy_(rnd((N, Hkv, D), 1.0))
-        vp.copy_(rnd((N, Hkv, D), 1.0))
+        if args.kv_pool == "pinned":
+            kp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
+            vp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
+            kp.copy_(rnd((N, Hkv, D), 1.0))
+            vp.copy_(rnd((N, Hkv, D), 1.0))
+        else:
+            kp, vp = rnd((N, Hkv, D), 1.0), rnd((N, Hkv, D), 1.0)
         pools.append((kp, vp))
     torch.cuda.synchronize()
 
@@ -174,7 +177,8 @@ def bench_stack(args, B, W, np, torch) -> int:
         entries, keep = [], []
         for lw, (kp, vp) in zip(weights, pools):
             ch = B.make_chunks([dict(k=kp[c * sp.chunk_len:(c + 1) * sp.chunk_len], v=vp[c * sp.chunk_len:(c + 1) * sp.chunk_len],
-                                     n_tokens=sp.chunk_len, old_pos_start=0, new_pos_start=c * sp.chunk_len, location=1)
+                                     n_tokens=sp.chunk_len, old_pos_start=0, new_pos_start=c * sp.chunk_len,
+                                     location=1 if args.kv_pool == "pinned" else 0)
                                 for c in range(sp.n_chunks)])
             keep.append(ch)
             d = dict(lw)
@@ -197,28 +201,39 @@ def bench_stack(args, B, W, np, torch) -> int:
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
+        B.ct_profile_reset()
+        B.ct_set_profiling(not args.no_profile_events)
         t0 = time.perf_counter()
         for _ in range(steps):
             step()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
+        B.ct_set_profiling(False)
+        kern = {}
+        for name in B.KERNEL_CLASSES:
+            cnt, kms = B.ct_profile_read(name)
+            if cnt:
+                kern[name] = {"launches_per_layer": cnt / steps / n_layers, "ms_per_layer": kms / steps / n_layers}
+        B.ct_profile_reset()
         assert torch.isfinite(h.float()).all()
-        return ms, n_sel
+        return ms, n_sel, kern
 
     log(f"partial prefill r={sp.ratio_pct}%")
-    ms_part, n_sel = run(sp.ratio_pct, args.steps, args.warmup)
+    ms_part, n_sel, kern_part = run(sp.ratio_pct, args.steps, args.warmup)
     log("full prefill (r=100%)")
-    ms_full, _ = run(100, max(1, args.steps // 4), 1)
+    ms_full, _, kern_full = run(100, max(1, args.steps // 4), 1)
     line = {
         "metric": f"end-to-end partial prefill latency, {n_layers}-layer stack @{N // 1024}K ctx, r={sp.ratio_pct}% (vs full prefill)",
         "value": ms_part, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_part, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": sp.name, "layers": n_layers, "n_ctx": N, "n_sel": n_sel, "ffn_dim": ffn,
-                   "kv_pool": "pinned host, streamed one layer ahead on a second stream"},
+                   "kv_pool": "pinned host, streamed one layer ahead on a second stream" if args.kv_pool == "pinned"
+                   else "device-resident"},
         "extra": {"full_prefill_ms": ms_full, "speedup_vs_full_prefill": ms_full / ms_part,
                   "ms_per_layer_partial": ms_part / n_layers, "ms_per_layer_full": ms_full / n_layers,
-                  "host_to_device_bytes_per_layer": 2 * N * Hkv * D * 2},
+                  "host_to_device_bytes_per_layer": 2 * N * Hkv * D * 2 if args.kv_pool == "pinned" else 0,
+                  "kernels_partial": kern_part, "kernels_full": kern_full},
     }
     print(json.dumps(line), flush=True)
     return 0
@@ -229,8 +244,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5])
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: number of layers")
+    ap.add_argument("--kv-pool", choices=["pinned", "device"], default="pinned",
+                    help="config 5 only: where the per-layer cached K/V live (pinned host memory is the paper's CPU pool)")
     ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=96)
@@ -275,13 +292,22 @@ def main() -> int:
     hidden, wqkv = dev(wl.hidden), dev(wl.wqkv)
     rows = None if wl.hidden_rows is None else torch.from_numpy(wl.hidden_rows).cuda()
     sel = torch.from_numpy(wl.sel_idx).cuda()
-    k_pool, v_pool = dev(wl.k_cache), dev(wl.v_cache)
-    k_buf, v_buf = torch.zeros_like(k_pool), torch.zeros_like(v_pool)
+    host_pool = args.config == 4      # config 4 keeps the cached K/V in pinned host memory
+    if host_pool:
+        def pin(bits):
+            t = torch.empty(bits.shape, dtype=torch.int16, pin_memory=True)
+            t.copy_(torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)))
+            return t.view(torch.bfloat16)
+        k_pool, v_pool = pin(wl.k_cache), pin(wl.v_cache)
+    else:
+        k_pool, v_pool = dev(wl.k_cache), dev(wl.v_cache)
+    k_buf = torch.zeros(k_pool.shape, dtype=torch.bfloat16, device="cuda")
+    v_buf = torch.zeros_like(k_buf)
     chunks = B.make_chunks([
         dict(k=k_pool[int(wl.chunk_rows[c]):int(wl.chunk_rows[c + 1])],
              v=v_pool[int(wl.chunk_rows[c]):int(wl.chunk_rows[c + 1])],
              n_tokens=int(wl.chunk_rows[c + 1] - wl.chunk_rows[c]), old_pos_start=int(wl.chunk_old_start[c]),
-             new_pos_start=int(wl.chunk_new_start[c]), location=0) for c in range(sp.n_chunks)])
+             new_pos_start=int(wl.chunk_new_start[c]), location=1 if host_pool else 0) for c in range(sp.n_chunks)])
     ws_bytes = B.ct_workspace_bytes(cfg, sp.n_ctx, sp.n_sel)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
     out = torch.zeros((sp.n_sel, sh.n_q_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
@@ -356,7 +382,10 @@ def main() -> int:
     if "scatter" in kern:
         extra["scatter_gbs"] = scatter_bytes / (kern["scatter"]["ms_per_step"] * 1e-3) / 1e9
 
-    if not args.no_cold_cache:
+    if host_pool:
+        extra["host_to_device_bytes_per_step"] = 4 * N * Hkv * D
+        extra["host_link_gbs_if_transfer_bound"] = 4.0 * N * Hkv * D / (ms_per_step * 1e-3) / 1e9
+    if not args.no_cold_cache and not host_pool:
         extra["cold_cache"] = cold_cache_bandwidth(B, cfg, wl, sp, torch, np)
 
     cpu = None
@@ -372,7 +401,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": sp.name, "n_ctx": N, "n_chunks": sp.n_chunks, "chunk_len": sp.chunk_len,
                    "recompute_ratio": ratio, "n_sel": n, "hidden": E, "heads": f"{Hq}/{Hkv}", "head_dim": D,
-                   "kv_pool": "device-resident, rotated + copied into the layer buffers each step"},
+                   "kv_pool": "pinned host memory, streamed in and rotated by a kernel on a second stream each step"
+                   if host_pool else "device-resident, rotated + copied into the layer buffers each step"},
         "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
     }
     print(json.dumps(line), flush=True)

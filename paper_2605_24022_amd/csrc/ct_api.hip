@@ -140,6 +140,79 @@ static ct_status check_indices_host(const int32_t* idx, int32_t n_sel, int32_t n
   return CT_OK;
 }
 
+// Device-visible address of pinned host memory, or nullptr when `p` is not mapped for the device
+// (pageable memory, or anything the runtime does not know).
+static const void* device_view_of_host(const void* p) {
+  hipPointerAttribute_t attr;
+  memset(&attr, 0, sizeof(attr));
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+    (void)hipGetLastError();   // unknown pointer: not an error of ours
+    return nullptr;
+  }
+  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return nullptr;
+  return attr.devicePointer;
+}
+
+// Workgroups (of 1024 threads) of the stream-in kernel.  Eight keep the host link at about 55 GB/s
+// on MI355X (four: 45 GB/s); every further one takes a compute unit away from the kernels of the recompute
+// stream and slows them more than the faster transfer gains.
+static int stream_in_blocks() {
+  static const int v = []() {
+    const char* e = getenv("CT_STREAM_IN_BLOCKS");
+    const int n = e != nullptr ? atoi(e) : 0;
+    return n > 0 ? n : 8;
+  }();
+  return v;
+}
+
+ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
+                                void* k_buf, void* v_buf, hipStream_t xs, bool* done) {
+  *done = false;
+  static const bool enabled = []() {
+    const char* e = getenv("CT_STREAM_IN");
+    return e == nullptr || atoi(e) != 0;
+  }();
+  if (!enabled) return CT_OK;
+  const void* kview[64];
+  const void* vview[64];
+  for (int c = 0; c < n_chunks; ++c) {
+    if (chunks[c].location != 1) continue;
+    kview[c] = device_view_of_host(chunks[c].k);
+    vview[c] = device_view_of_host(chunks[c].v);
+    if (kview[c] == nullptr || vview[c] == nullptr) return CT_OK;   // caller falls back to copies
+  }
+  ReropeChunks rc;
+  memset(&rc, 0, sizeof(rc));
+  auto flush = [&]() -> ct_status {
+    if (rc.n == 0) return CT_OK;
+    rc.tok_start[rc.n] = rc.total_tokens;
+    ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, stream_in_blocks(), xs);
+    rc.n = 0;
+    rc.total_tokens = 0;
+    return r;
+  };
+  for (int c = 0; c < n_chunks; ++c) {
+    const ct_chunk& ch = chunks[c];
+    if (ch.location != 1) continue;
+    const int i = rc.n++;
+    rc.tok_start[i] = rc.total_tokens;
+    rc.total_tokens += ch.n_tokens;
+    rc.k_src[i] = kview[c];
+    rc.v_src[i] = vview[c];
+    rc.row_start[i] = tab.row_start[c];
+    rc.delta0[i] = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
+    rc.delta_step[i] = ch.raw_keys ? 1 : 0;
+    if (rc.n == 32) {
+      ct_status st = flush();
+      if (st != CT_OK) return st;
+    }
+  }
+  ct_status st = flush();
+  if (st != CT_OK) return st;
+  *done = true;
+  return CT_OK;
+}
+
 }  // namespace ct
 
 using namespace ct;
@@ -351,6 +424,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   // Transfer stream: enqueue every pinned-host chunk's copy first so the DMA engine starts
   // at once; one event per chunk lets the compute stream rotate chunk c as soon as it lands.
   std::vector<hipEvent_t> landed;
+  bool streamed = false;
   hipError_t e;
   if (any_host) {
     // the copies write k_buf / v_buf: they must not overtake earlier work of the compute
@@ -361,8 +435,21 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     if (e == hipSuccess) e = hipStreamWaitEvent(xs, fence, 0);
     (void)hipEventDestroy(fence);
     if (e != hipSuccess) return hip_fail(e, "fence compute->copy stream");
+    // Preferred: a kernel on the transfer stream reads the pinned chunks over the host link,
+    // rotates the keys on the way and writes keys and values to their buffer rows (Eq. 8 overlapped
+    // with the transfer); one event says that all of them are in place.
+    if ((st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, xs, &streamed)) != CT_OK) return st;
     landed.resize(n_chunks, nullptr);
-    for (int c = 0; c < n_chunks; ++c) {
+    if (streamed) {
+      e = hipEventCreateWithFlags(&landed[0], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventRecord(landed[0], xs);
+      if (e != hipSuccess) {
+        if (landed[0]) (void)hipEventDestroy(landed[0]);
+        return hip_fail(e, "event after the stream-in kernel");
+      }
+    }
+    // Otherwise (host memory the device cannot address): plain copies, one event per chunk.
+    for (int c = 0; c < n_chunks && !streamed; ++c) {
       const ct_chunk& ch = chunks[c];
       if (ch.location != 1) continue;
       char* kd = static_cast<char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;
@@ -399,7 +486,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     auto flush = [&]() -> ct_status {
       if (rc.n == 0) return CT_OK;
       rc.tok_start[rc.n] = rc.total_tokens;
-      ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, cs);
+      ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, 0, cs);
       rc.n = 0;
       rc.total_tokens = 0;
       return r;
@@ -429,8 +516,13 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
       return st;
     }
   }
-  // Pinned-host chunks: rotate chunk c in place as soon as its copy has landed.
-  for (int c = 0; c < n_chunks; ++c) {
+  // Pinned-host chunks: already rotated by the stream-in kernel, or rotated in place chunk by
+  // chunk as soon as each copy has landed.
+  if (streamed && (e = hipStreamWaitEvent(cs, landed[0], 0)) != hipSuccess) {
+    drop_events();
+    return hip_fail(e, "hipStreamWaitEvent (chunks streamed in)");
+  }
+  for (int c = 0; c < n_chunks && !streamed; ++c) {
     const ct_chunk& ch = chunks[c];
     if (ch.location != 1) continue;
     char* kd = static_cast<char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;

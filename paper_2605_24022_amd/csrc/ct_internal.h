@@ -53,8 +53,16 @@ struct ReropeChunks {
   int32_t delta0[32];
   int32_t delta_step[32];
 };
+// max_blocks > 0 caps the grid (threads then stride over the tokens).
 ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
-                               hipStream_t s);
+                               int max_blocks, hipStream_t s);
+// Pinned-host chunks (location 1) read by a kernel on stream `xs` straight from host memory:
+// keys rotated on the way, values copied, both written to their rows of the layer buffers.
+// *done is false, and nothing was enqueued, when some chunk's memory is not addressable by the
+// device; the caller then copies.
+struct ChunkTable;
+ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
+                                void* k_buf, void* v_buf, hipStream_t xs, bool* done);
 ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
                          const int32_t* sel_idx, int32_t n_sel, hipStream_t s);
 // pos_of_row != NULL: position of selected token s is pos_of_row[s]; otherwise it is looked up

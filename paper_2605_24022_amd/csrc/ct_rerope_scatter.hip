@@ -118,16 +118,21 @@ __global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
                                 v_dst ? v_dst + row : nullptr, delta, jg, n_heads_rt, table);
 }
 
-// Several chunks in one launch: buffer row -> chunk by search in the (small) table.
-template <int D, int STYLE, int HEADS>
-__global__ __launch_bounds__(kReropeThreads) void rerope_chunks_kernel(uint16_t* k_buf, uint16_t* v_buf,
-                                                                      int32_t n_heads_rt, RopeTable table,
-                                                                      ReropeChunks chunks) {
+// Several chunks in one launch: buffer row -> chunk by search in the (small) table.  The grid may
+// be smaller than the token count (the launcher caps it for sources in pinned host memory, where
+// a few workgroups already keep the host link busy and every further one only takes a compute
+// unit away from the kernels of the recompute stream); threads then stride over the tokens.
+// THREADS: 256, or 1024 for the capped launches - the loads of a thread that are in flight at a
+// time are what the long latency of the host link has to be covered with, and sixteen waves on
+// one compute unit cost the other stream no more than four do.
+template <int D, int STYLE, int HEADS, int THREADS>
+__global__ __launch_bounds__(THREADS) void rerope_chunks_kernel(uint16_t* k_buf, uint16_t* v_buf, int32_t n_heads_rt,
+                                                                RopeTable table, ReropeChunks chunks) {
   constexpr int GROUPS = D / 16;
-  const int64_t gid = (int64_t)blockIdx.x * kReropeThreads + threadIdx.x;
-  const int64_t t_all = gid / GROUPS;      // ordinal among the tokens of the listed chunks
+  const int64_t gid = (int64_t)blockIdx.x * THREADS + threadIdx.x;
   const int jg = (int)(gid % GROUPS);
-  if (t_all >= chunks.total_tokens) return;
+  const int64_t t_step = (int64_t)gridDim.x * (THREADS / GROUPS);
+  for (int64_t t_all = gid / GROUPS; t_all < chunks.total_tokens; t_all += t_step) {   // ordinal among the listed tokens
   int c = 0;
   while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
   const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
@@ -138,6 +143,7 @@ __global__ __launch_bounds__(kReropeThreads) void rerope_chunks_kernel(uint16_t*
   const uint16_t* vs = chunks.v_src[c] ? static_cast<const uint16_t*>(chunks.v_src[c]) + src_row : nullptr;
   const int32_t delta = chunks.delta0[c] + chunks.delta_step[c] * t;
   rerope_token<D, STYLE, HEADS>(ks, k_buf + dst_row, vs, v_buf + dst_row, delta, jg, n_heads_rt, table);
+  }
 }
 
 // One 16-byte piece per thread and loop step; a selected row's K and V are `row_vec`
@@ -162,10 +168,13 @@ __global__ __launch_bounds__(256) void scatter_kernel(u32x4* __restrict__ k_buf,
 template <int D, int STYLE, int HEADS>
 void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* kd, const uint16_t* vs, uint16_t* vd,
                        const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep, int32_t n, int H,
-                       const RopeTable& t, const ReropeChunks* chunks) {
+                       const RopeTable& t, const ReropeChunks* chunks, bool big_blocks) {
   if (chunks != nullptr) {
-    hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
-                       *chunks);
+    if (big_blocks)
+      hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS, 1024>), grid, dim3(1024), 0, s, kd, vd, H, t, *chunks);
+    else
+      hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS, kReropeThreads>), grid, dim3(kReropeThreads), 0, s, kd,
+                         vd, H, t, *chunks);
   } else {
     hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op, np, d0,
                        dstep, n, H, t);
@@ -175,35 +184,39 @@ void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* k
 template <int D, int STYLE>
 void launch_rerope_heads(int H, dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* kd, const uint16_t* vs,
                          uint16_t* vd, const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep, int32_t n,
-                         const RopeTable& t, const ReropeChunks* chunks) {
+                         const RopeTable& t, const ReropeChunks* chunks, bool big_blocks) {
   if (H == 8)
-    launch_rerope_one<D, STYLE, 8>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks);
+    launch_rerope_one<D, STYLE, 8>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks, big_blocks);
   else if (H == 2)
-    launch_rerope_one<D, STYLE, 2>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks);
+    launch_rerope_one<D, STYLE, 2>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks, big_blocks);
   else
-    launch_rerope_one<D, STYLE, 0>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks);
+    launch_rerope_one<D, STYLE, 0>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks, big_blocks);
 }
 
 ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_t* kd, const uint16_t* vs,
                             uint16_t* vd, const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep,
-                            int64_t n_tokens, const ReropeChunks* chunks, hipStream_t s) {
+                            int64_t n_tokens, const ReropeChunks* chunks, int max_blocks, hipStream_t s) {
   if (n_tokens == 0) return CT_OK;
   RopeTable table;
   fill_rope_table(cfg, &table);
   const int D = cfg->head_dim, H = cfg->n_kv_heads;
   const int64_t threads = n_tokens * (D / 16);
-  dim3 grid((unsigned)((threads + kReropeThreads - 1) / kReropeThreads));
+  const bool big_blocks = chunks != nullptr && max_blocks > 0;
+  const int per_block = big_blocks ? 1024 : kReropeThreads;
+  int64_t blocks = (threads + per_block - 1) / per_block;
+  if (big_blocks && blocks > max_blocks) blocks = max_blocks;
+  dim3 grid((unsigned)blocks);
   int slot = prof_begin(KC_REROPE, s);
   if (D == 128) {
     if (cfg->rope_style == 0)
-      launch_rerope_heads<128, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+      launch_rerope_heads<128, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
     else
-      launch_rerope_heads<128, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+      launch_rerope_heads<128, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
   } else {
     if (cfg->rope_style == 0)
-      launch_rerope_heads<64, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+      launch_rerope_heads<64, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
     else
-      launch_rerope_heads<64, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks);
+      launch_rerope_heads<64, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
   }
   prof_end(KC_REROPE, slot, s);
   hipError_t e = hipGetLastError();
@@ -218,13 +231,13 @@ ct_status launch_rerope(const ct_layer_cfg* cfg, const void* k_src, void* k_dst,
                         int32_t n_tokens, hipStream_t s) {
   return launch_rerope_any(cfg, static_cast<const uint16_t*>(k_src), static_cast<uint16_t*>(k_dst),
                            static_cast<const uint16_t*>(v_src), static_cast<uint16_t*>(v_dst), old_pos, new_pos,
-                           delta0, delta_step, n_tokens, nullptr, s);
+                           delta0, delta_step, n_tokens, nullptr, 0, s);
 }
 
 ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
-                               hipStream_t s) {
+                               int max_blocks, hipStream_t s) {
   return launch_rerope_any(cfg, nullptr, static_cast<uint16_t*>(k_buf), nullptr, static_cast<uint16_t*>(v_buf),
-                           nullptr, nullptr, 0, 0, chunks->total_tokens, chunks, s);
+                           nullptr, nullptr, 0, 0, chunks->total_tokens, chunks, max_blocks, s);
 }
 
 ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,

@@ -241,6 +241,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
 
   // Transfer stream: layer l's pinned-host chunks go to buffer slot l & 1.  The copies may start as
   // soon as the attention of layer l - 2 (the previous user of that slot) is done.
+  bool streamed[2] = {false, false};
   auto enqueue_copies = [&](int l) -> ct_status {
     if (full || !any_host) return CT_OK;
     if (l >= 2) {
@@ -252,6 +253,15 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     }
     char* kb = static_cast<char*>(k_bufs) + (size_t)(l & 1) * buf_bytes;
     char* vb = static_cast<char*>(v_bufs) + (size_t)(l & 1) * buf_bytes;
+    // preferred: one kernel streams the chunks in and rotates the keys on the way
+    bool done = false;
+    ct_status sst = stream_in_host_chunks(cfg, layers[l].chunks, n_chunks, tab, kb, vb, xs, &done);
+    if (sst != CT_OK) return sst;
+    streamed[l & 1] = done;
+    if (done) {
+      if ((e = hipEventRecord(landed(l, 0), xs)) != hipSuccess) return hip_fail(e, "hipEventRecord (chunks streamed in)");
+      return CT_OK;
+    }
     for (int c = 0; c < n_chunks; ++c) {
       const ct_chunk& ch = layers[l].chunks[c];
       if (ch.location != 1) continue;
@@ -283,7 +293,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
       auto flush = [&]() -> ct_status {
         if (rc.n == 0) return CT_OK;
         rc.tok_start[rc.n] = rc.total_tokens;
-        ct_status r = launch_rerope_chunks(cfg, kb, vb, &rc, cs);
+        ct_status r = launch_rerope_chunks(cfg, kb, vb, &rc, 0, cs);
         rc.n = 0;
         rc.total_tokens = 0;
         return r;
@@ -302,7 +312,9 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
         if (rc.n == 32 && (st = flush()) != CT_OK) return st;
       }
       if ((st = flush()) != CT_OK) return st;
-      for (int c = 0; c < n_chunks; ++c) {
+      if (streamed[l & 1] && (e = hipStreamWaitEvent(cs, landed(l, 0), 0)) != hipSuccess)
+        return hip_fail(e, "hipStreamWaitEvent (chunks streamed in)");
+      for (int c = 0; c < n_chunks && !streamed[l & 1]; ++c) {
         const ct_chunk& ch = lw.chunks[c];
         if (ch.location != 1) continue;
         if ((e = hipStreamWaitEvent(cs, landed(l, c), 0)) != hipSuccess) return hip_fail(e, "hipStreamWaitEvent (chunk landed)");

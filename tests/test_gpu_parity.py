@@ -188,7 +188,7 @@ def test_selected_attention_clustered_rows():
 
 
 # ------------------------------------------------------------------------------ whole layer
-def _run_layer(wl, pinned=False, poison=True, in_place=False):
+def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False):
     sp, sh = wl.spec, wl.spec.shape
     cfg = B.cfg_from_shape(sh)
     n_ctx, n_sel = sp.n_ctx, sp.n_sel
@@ -203,7 +203,11 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False):
     fill = float("nan") if poison else 0.0
     k_buf = torch.full((n_ctx, sh.n_kv_heads, sh.head_dim), fill, dtype=torch.bfloat16, device="cuda")
     v_buf = torch.full((n_ctx, sh.n_kv_heads, sh.head_dim), fill, dtype=torch.bfloat16, device="cuda")
-    if pinned:
+    if pageable:   # ordinary host memory the device cannot address: the library has to copy
+        k_pool = torch.from_numpy(np.ascontiguousarray(k_cache).view(np.int16)).view(torch.bfloat16)
+        v_pool = torch.from_numpy(np.ascontiguousarray(v_cache).view(np.int16)).view(torch.bfloat16)
+        pinned = True
+    elif pinned:
         k_pool, v_pool = pinned_bf16(k_cache), pinned_bf16(v_cache)
     elif in_place:
         k_buf.copy_(dev_bf16(k_cache)); v_buf.copy_(dev_bf16(v_cache))
@@ -249,10 +253,11 @@ def _check_layer(wl, out, k_buf, v_buf, rows=None):
     assert_close(f64_of(v_buf)[wl.sel_idx], v_want[wl.sel_idx], f"{wl.spec.name} recomputed V")
 
 
-@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned"])
+@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned", "pageable"])
 def test_layer_config1(mode):
     wl = W.make_workload(W.spec(1))
-    out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place")
+    out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place",
+                             pageable=mode == "pageable")
     _check_layer(wl, out, kb, vb)
 
 
