@@ -53,6 +53,10 @@ struct ReropeChunks {
   int32_t delta0[32];
   int32_t delta_step[32];
 };
+// LDS that the small kernels of the recompute stream claim without using it (the large ones need
+// at least as much anyway): together with the 80 KiB the stream-in kernel claims, it keeps the two
+// streams' workgroups on different compute units.
+constexpr int kKeepOutLdsBytes = 96 * 1024;
 // max_blocks > 0 caps the grid (threads then stride over the tokens).
 ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
                                int max_blocks, hipStream_t s);

@@ -118,41 +118,74 @@ __global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
                                 v_dst ? v_dst + row : nullptr, delta, jg, n_heads_rt, table);
 }
 
-// Several chunks in one launch: buffer row -> chunk by search in the (small) table.  The grid may
-// be smaller than the token count (the launcher caps it for sources in pinned host memory, where
-// a few workgroups already keep the host link busy and every further one only takes a compute
-// unit away from the kernels of the recompute stream); threads then stride over the tokens.
-// THREADS: 256, or 1024 for the capped launches - the loads of a thread that are in flight at a
-// time are what the long latency of the host link has to be covered with, and sixteen waves on
-// one compute unit cost the other stream no more than four do.
-template <int D, int STYLE, int HEADS, int THREADS>
-__global__ __launch_bounds__(THREADS) void rerope_chunks_kernel(uint16_t* k_buf, uint16_t* v_buf, int32_t n_heads_rt,
-                                                                RopeTable table, ReropeChunks chunks) {
+// Several chunks in one launch: buffer row -> chunk by search in the (small) table.
+template <int D, int STYLE, int HEADS>
+__device__ __forceinline__ void rerope_chunk_tokens(uint16_t* k_buf, uint16_t* v_buf, int32_t n_heads_rt,
+                                                    const RopeTable& table, const ReropeChunks& chunks, int threads) {
   constexpr int GROUPS = D / 16;
-  const int64_t gid = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  const int64_t gid = (int64_t)blockIdx.x * threads + threadIdx.x;
   const int jg = (int)(gid % GROUPS);
-  const int64_t t_step = (int64_t)gridDim.x * (THREADS / GROUPS);
+  const int64_t t_step = (int64_t)gridDim.x * (threads / GROUPS);
   for (int64_t t_all = gid / GROUPS; t_all < chunks.total_tokens; t_all += t_step) {   // ordinal among the listed tokens
-  int c = 0;
-  while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
-  const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
-  const int64_t heads = HEADS > 0 ? HEADS : n_heads_rt;
-  const int64_t src_row = (int64_t)t * heads * D;
-  const int64_t dst_row = ((int64_t)chunks.row_start[c] + t) * heads * D;
-  const uint16_t* ks = static_cast<const uint16_t*>(chunks.k_src[c]) + src_row;
-  const uint16_t* vs = chunks.v_src[c] ? static_cast<const uint16_t*>(chunks.v_src[c]) + src_row : nullptr;
-  const int32_t delta = chunks.delta0[c] + chunks.delta_step[c] * t;
-  rerope_token<D, STYLE, HEADS>(ks, k_buf + dst_row, vs, v_buf + dst_row, delta, jg, n_heads_rt, table);
+    int c = 0;
+    while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
+    const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
+    const int64_t heads = HEADS > 0 ? HEADS : n_heads_rt;
+    const int64_t src_row = (int64_t)t * heads * D;
+    const int64_t dst_row = ((int64_t)chunks.row_start[c] + t) * heads * D;
+    const uint16_t* ks = static_cast<const uint16_t*>(chunks.k_src[c]) + src_row;
+    const uint16_t* vs = chunks.v_src[c] ? static_cast<const uint16_t*>(chunks.v_src[c]) + src_row : nullptr;
+    const int32_t delta = chunks.delta0[c] + chunks.delta_step[c] * t;
+    rerope_token<D, STYLE, HEADS>(ks, k_buf + dst_row, vs, v_buf + dst_row, delta, jg, n_heads_rt, table);
   }
+}
+
+template <int D, int STYLE, int HEADS>
+__global__ __launch_bounds__(kReropeThreads) void rerope_chunks_kernel(uint16_t* k_buf, uint16_t* v_buf,
+                                                                      int32_t n_heads_rt, RopeTable table,
+                                                                      ReropeChunks chunks) {
+  rerope_chunk_tokens<D, STYLE, HEADS>(k_buf, v_buf, n_heads_rt, table, chunks, kReropeThreads);
+}
+
+// The same work for chunks in pinned host memory, read over the host link by a few resident
+// workgroups that stride over the tokens (Sec. 4.2: RoPE recovery overlapped with the transfer).
+// What it is shaped by, measured on MI355X:
+//  - a load from host memory takes microseconds, and while it is pending it holds a slot in the
+//    memory pipeline of its compute unit and in the L2 channel's queue to the fabric; waves of
+//    other kernels on the same compute unit, and L2 misses of any kernel in the same XCD, wait
+//    behind it.  So a thread keeps only one head's two 16-byte loads in flight (about 128 KiB
+//    over the whole grid already keeps the link at 45-50 GB/s; more only lengthens the queues);
+//  - the 80 KiB of LDS are not used: they keep the workgroups of the GEMM and attention kernels,
+//    which need 96-160 KiB, off the few compute units this kernel sits on, where they would run
+//    at the speed of the host link.
+constexpr int kStreamInThreads = 1024;
+constexpr int kStreamInLdsBytes = 80 * 1024;
+template <int D, int STYLE>
+__global__ __launch_bounds__(kStreamInThreads) void stream_in_kernel(uint16_t* k_buf, uint16_t* v_buf, int32_t n_heads_rt,
+                                                                    RopeTable table, ReropeChunks chunks) {
+  __shared__ unsigned char keep_out[kStreamInLdsBytes];
+  if (chunks.n < 0) {   // never true; keeps the allocation
+    keep_out[threadIdx.x * 64] = (unsigned char)threadIdx.x;
+    __syncthreads();
+    k_buf[threadIdx.x] = keep_out[(threadIdx.x * 64 + 64) % kStreamInLdsBytes];
+  }
+  rerope_chunk_tokens<D, STYLE, 0>(k_buf, v_buf, n_heads_rt, table, chunks, kStreamInThreads);
 }
 
 // One 16-byte piece per thread and loop step; a selected row's K and V are `row_vec`
 // pieces each.  Pieces of consecutive threads are consecutive in memory.
-__global__ __launch_bounds__(256) void scatter_kernel(u32x4* __restrict__ k_buf, u32x4* __restrict__ v_buf,
-                                                     const u32x4* __restrict__ k_sel,
-                                                     const u32x4* __restrict__ v_sel,
-                                                     const int32_t* __restrict__ sel_idx, int32_t n_sel,
-                                                     int32_t row_vec) {
+// The LDS is claimed, not used: see kKeepOutLdsBytes.
+__global__ __launch_bounds__(1024) void scatter_kernel(u32x4* __restrict__ k_buf, u32x4* __restrict__ v_buf,
+                                                      const u32x4* __restrict__ k_sel,
+                                                      const u32x4* __restrict__ v_sel,
+                                                      const int32_t* __restrict__ sel_idx, int32_t n_sel,
+                                                      int32_t row_vec) {
+  __shared__ unsigned char keep_out[kKeepOutLdsBytes];
+  if (row_vec < 0) {   // never true; keeps the allocation
+    keep_out[threadIdx.x * 64] = (unsigned char)threadIdx.x;
+    __syncthreads();
+    k_buf[threadIdx.x][0] = keep_out[(threadIdx.x * 64 + 64) % kKeepOutLdsBytes];
+  }
   const int64_t total = (int64_t)n_sel * row_vec;
   for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (int64_t)gridDim.x * blockDim.x) {
     const int64_t s = p / row_vec;
@@ -171,10 +204,10 @@ void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* k
                        const RopeTable& t, const ReropeChunks* chunks, bool big_blocks) {
   if (chunks != nullptr) {
     if (big_blocks)
-      hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS, 1024>), grid, dim3(1024), 0, s, kd, vd, H, t, *chunks);
+      hipLaunchKernelGGL((stream_in_kernel<D, STYLE>), grid, dim3(kStreamInThreads), 0, s, kd, vd, H, t, *chunks);
     else
-      hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS, kReropeThreads>), grid, dim3(kReropeThreads), 0, s, kd,
-                         vd, H, t, *chunks);
+      hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
+                         *chunks);
   } else {
     hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op, np, d0,
                        dstep, n, H, t);
@@ -201,8 +234,8 @@ ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_
   fill_rope_table(cfg, &table);
   const int D = cfg->head_dim, H = cfg->n_kv_heads;
   const int64_t threads = n_tokens * (D / 16);
-  const bool big_blocks = chunks != nullptr && max_blocks > 0;
-  const int per_block = big_blocks ? 1024 : kReropeThreads;
+  const bool big_blocks = chunks != nullptr && max_blocks > 0;   // sources in pinned host memory
+  const int per_block = big_blocks ? kStreamInThreads : kReropeThreads;
   int64_t blocks = (threads + per_block - 1) / per_block;
   if (big_blocks && blocks > max_blocks) blocks = max_blocks;
   dim3 grid((unsigned)blocks);
@@ -245,10 +278,10 @@ ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, cons
   if (n_sel == 0) return CT_OK;
   const int row_vec = cfg->n_kv_heads * cfg->head_dim / 8;  // 16-byte pieces per row
   const int64_t total = (int64_t)n_sel * row_vec;
-  int64_t blocks = (total + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
+  int64_t blocks = (total + 1023) / 1024;
+  if (blocks > 2048) blocks = 2048;
   int slot = prof_begin(KC_SCATTER, s);
-  hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<u32x4*>(k_buf),
+  hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)blocks), dim3(1024), 0, s, static_cast<u32x4*>(k_buf),
                      static_cast<u32x4*>(v_buf), static_cast<const u32x4*>(k_sel), static_cast<const u32x4*>(v_sel),
                      sel_idx, n_sel, row_vec);
   prof_end(KC_SCATTER, slot, s);

@@ -18,10 +18,22 @@ namespace ct {
 namespace {
 
 // One wave per row: sum of squares in fp32, wave reduction, second pass scales and rounds.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
-                                                     uint16_t* __restrict__ out, int32_t n_tok, int32_t width, float eps) {
+// The LDS is not used: claiming it keeps the workgroups off the compute units on which the
+// stream-in kernel of the transfer stream sits (which claims the other half), where every memory
+// access would wait behind that kernel's loads from host memory.
+constexpr int kNormRows = 16;
+__global__ __launch_bounds__(64 * kNormRows) void rmsnorm_kernel(const uint16_t* __restrict__ x,
+                                                                const uint16_t* __restrict__ w,
+                                                                uint16_t* __restrict__ out, int32_t n_tok, int32_t width,
+                                                                float eps) {
+  __shared__ unsigned char keep_out[kKeepOutLdsBytes];
+  if (width < 0) {   // never true; keeps the allocation
+    keep_out[threadIdx.x * 64] = (unsigned char)threadIdx.x;
+    __syncthreads();
+    out[threadIdx.x] = keep_out[(threadIdx.x * 64 + 64) % kKeepOutLdsBytes];
+  }
   const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t row = (int64_t)blockIdx.x * kNormRows + (threadIdx.x >> 6);
   if (row >= n_tok) return;
   const u32x4* xr = reinterpret_cast<const u32x4*>(x + row * width);
   const u32x4* wr = reinterpret_cast<const u32x4*>(w);
@@ -92,7 +104,7 @@ StackLayout stack_layout(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx
 ct_status launch_rmsnorm(const void* x, const void* w, float eps, int32_t n_tok, int32_t width, void* out, hipStream_t s) {
   if (n_tok == 0) return CT_OK;
   int slot = prof_begin(KC_NORM, s);
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3((n_tok + 3) / 4), dim3(256), 0, s, static_cast<const uint16_t*>(x),
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3((n_tok + kNormRows - 1) / kNormRows), dim3(64 * kNormRows), 0, s, static_cast<const uint16_t*>(x),
                      static_cast<const uint16_t*>(w), static_cast<uint16_t*>(out), n_tok, width, eps);
   prof_end(KC_NORM, slot, s);
   hipError_t e = hipGetLastError();
