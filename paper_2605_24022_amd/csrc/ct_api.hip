@@ -166,7 +166,8 @@ static int stream_in_blocks() {
 }
 
 ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
-                                void* k_buf, void* v_buf, hipStream_t xs, bool* done) {
+                                void* k_buf, void* v_buf, const int32_t* sel_idx, int32_t n_sel, hipStream_t xs,
+                                bool* done) {
   *done = false;
   static const bool enabled = []() {
     const char* e = getenv("CT_STREAM_IN");
@@ -183,9 +184,15 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
   }
   ReropeChunks rc;
   memset(&rc, 0, sizeof(rc));
+  static const bool skip_selected = []() {
+    const char* e = getenv("CT_STREAM_IN_SKIP_SELECTED");
+    return e == nullptr || atoi(e) != 0;
+  }();
   auto flush = [&]() -> ct_status {
     if (rc.n == 0) return CT_OK;
     rc.tok_start[rc.n] = rc.total_tokens;
+    rc.skip_rows = skip_selected && n_sel > 0 ? sel_idx : nullptr;
+    rc.n_skip = n_sel;
     ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, stream_in_blocks(), xs);
     rc.n = 0;
     rc.total_tokens = 0;
@@ -438,7 +445,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     // Preferred: a kernel on the transfer stream reads the pinned chunks over the host link,
     // rotates the keys on the way and writes keys and values to their buffer rows (Eq. 8 overlapped
     // with the transfer); one event says that all of them are in place.
-    if ((st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, xs, &streamed)) != CT_OK) return st;
+    if ((st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, sel_idx, n_sel, xs, &streamed)) != CT_OK) return st;
     landed.resize(n_chunks, nullptr);
     if (streamed) {
       e = hipEventCreateWithFlags(&landed[0], hipEventDisableTiming);

@@ -52,6 +52,8 @@ struct ReropeChunks {
   int32_t row_start[32];   // buffer row the chunk's first token goes to
   int32_t delta0[32];
   int32_t delta_step[32];
+  const int32_t* skip_rows;   // optional: sorted buffer rows that are not to be brought in (device memory)
+  int32_t n_skip;
 };
 // LDS that the small kernels of the recompute stream claim without using it (the large ones need
 // at least as much anyway): together with the 80 KiB the stream-in kernel claims, it keeps the two
@@ -65,8 +67,11 @@ ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf
 // *done is false, and nothing was enqueued, when some chunk's memory is not addressable by the
 // device; the caller then copies.
 struct ChunkTable;
+// Rows listed in sel_idx (the recompute set: their K/V are overwritten by the scatter) are not
+// transferred - the index-aware transfer of Sec. 4.2.
 ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
-                                void* k_buf, void* v_buf, hipStream_t xs, bool* done);
+                                void* k_buf, void* v_buf, const int32_t* sel_idx, int32_t n_sel, hipStream_t xs,
+                                bool* done);
 ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
                          const int32_t* sel_idx, int32_t n_sel, hipStream_t s);
 // pos_of_row != NULL: position of selected token s is pos_of_row[s]; otherwise it is looked up

@@ -130,6 +130,15 @@ __device__ __forceinline__ void rerope_chunk_tokens(uint16_t* k_buf, uint16_t* v
     int c = 0;
     while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
     const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
+    if (chunks.skip_rows != nullptr) {   // binary search for this buffer row in the sorted skip list
+      const int32_t row = chunks.row_start[c] + t;
+      int lo = 0, hi = chunks.n_skip;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (chunks.skip_rows[mid] < row) lo = mid + 1; else hi = mid;
+      }
+      if (lo < chunks.n_skip && chunks.skip_rows[lo] == row) continue;
+    }
     const int64_t heads = HEADS > 0 ? HEADS : n_heads_rt;
     const int64_t src_row = (int64_t)t * heads * D;
     const int64_t dst_row = ((int64_t)chunks.row_start[c] + t) * heads * D;

@@ -267,7 +267,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     char* vb = static_cast<char*>(v_bufs) + (size_t)(l & 1) * buf_bytes;
     // preferred: one kernel streams the chunks in and rotates the keys on the way
     bool done = false;
-    ct_status sst = stream_in_host_chunks(cfg, layers[l].chunks, n_chunks, tab, kb, vb, xs, &done);
+    ct_status sst = stream_in_host_chunks(cfg, layers[l].chunks, n_chunks, tab, kb, vb, sel_idx, n_sel, xs, &done);
     if (sst != CT_OK) return sst;
     streamed[l & 1] = done;
     if (done) {
