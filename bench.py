@@ -98,19 +98,22 @@ def cold_cache_bandwidth(B, cfg, wl, sp, torch, np, reps: int = 3):
     st = torch.cuda.current_stream()
     res = {"ring_buffers": ring, "ring_bytes": ring * N * row * 2 * 2}
 
-    def timed(name, fn):
+    def timed_on(bufs, name, fn):
         fn(0)
         torch.cuda.synchronize()
         B.ct_profile_reset()
         B.ct_set_profiling(True)
         for r in range(reps):
-            for i in range(ring):
+            for i in range(len(bufs)):
                 fn(i)
         torch.cuda.synchronize()
         B.ct_set_profiling(False)
         cnt, ms = B.ct_profile_read(name)
         B.ct_profile_reset()
         return ms / cnt * 1e-3
+
+    def timed(name, fn):
+        return timed_on(kb, name, fn)
 
     t = timed("rerope", lambda i: B.ct_rerope_keys(cfg, kb[i], kb[i], old, new, N, st))
     credited = 2.0 * (N - n) * row * 2 + 8.0 * (N - n)
@@ -133,6 +136,20 @@ def cold_cache_bandwidth(B, cfg, wl, sp, torch, np, reps: int = 3):
     torch.cuda.synchronize()
     t = e0.elapsed_time(e1) * 1e-3 / (reps * ring)
     res["plain_copy"] = {"avg_us": t * 1e6, "gbs": 2.0 * N * row * 2 / t / 1e9}
+    # the same in-place rotation on a 4x longer context (256 MiB of keys per launch), where the launch
+    # ramp weighs less
+    del vb
+    n4 = 4 * N
+    ring4 = max(2, ring // 4)
+    k4 = [torch.cat(kb[4 * i:4 * i + 4]) for i in range(ring4)] if ring >= 8 else None
+    if k4 is not None:
+        old4 = torch.arange(n4, device="cuda", dtype=torch.int32) % sp.chunk_len
+        new4 = torch.arange(n4, device="cuda", dtype=torch.int32)
+        t = timed_on(k4, "rerope", lambda i: B.ct_rerope_keys(cfg, k4[i], k4[i], old4, new4, n4, st))
+        m4 = 2.0 * n4 * row * 2 + 8.0 * n4
+        res["rerope_in_place_4x_tokens"] = {"n_tokens": n4, "avg_us": t * 1e6, "gbs_moved": m4 / t / 1e9,
+                                            "frac_of_hbm_peak_moved": m4 / t / 1e9 / PEAK_HBM_GBS}
+        del k4
     return res
 
 

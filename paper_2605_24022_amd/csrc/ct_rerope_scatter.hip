@@ -13,12 +13,27 @@ namespace {
 
 constexpr int kReropeThreads = 256;
 
+// Streaming accesses.  Cached keys and values are read once: their loads do not allocate in the
+// caches (measured cold: +3 % out of place).  A rotation in place also writes lines nobody reads
+// soon, so its stores bypass the caches as well (+17 % at 64 MiB, 5.3 -> 6.0 TB/s at 256 MiB);
+// rows written into a layer buffer are read by the attention kernel next and are stored normally.
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const uint16_t* p) {
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return *reinterpret_cast<const u32x4*>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void st16(uint16_t* p, u32x4 v) {
+  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+  else *reinterpret_cast<u32x4*>(p) = v;
+}
+
 // Rotate (and optionally copy V for) one token's share owned by this thread.
 // STYLE 0: pairs (j, j + D/2); STYLE 1: pairs (2j, 2j + 1).  HEADS > 0 fixes the head count
 // at compile time (full unroll, all loads in flight before the first use).
 // k_src/k_dst (and v_src/v_dst) may be the same row: a thread reads all it owns before it
 // writes, and no two threads own the same bytes.
-template <int D, int STYLE, int HEADS>
+template <int D, int STYLE, int HEADS, bool NT_STORE = false>
 __device__ __forceinline__ void rerope_token(const uint16_t* k_src, uint16_t* k_dst, const uint16_t* v_src,
                                              uint16_t* v_dst, int32_t delta, int jg, int n_heads_rt,
                                              const RopeTable& table) {
@@ -56,48 +71,48 @@ __device__ __forceinline__ void rerope_token(const uint16_t* k_src, uint16_t* k_
     u32x4 a[HEADS > 0 ? HEADS : 1], b[HEADS > 0 ? HEADS : 1];
 #pragma unroll
     for (int h = 0; h < HEADS; ++h) {
-      a[h] = *reinterpret_cast<const u32x4*>(k_src + h * D + off_a);
-      b[h] = *reinterpret_cast<const u32x4*>(k_src + h * D + off_b);
+      a[h] = ld16<true>(k_src + h * D + off_a);
+      b[h] = ld16<true>(k_src + h * D + off_b);
     }
 #pragma unroll
     for (int h = 0; h < HEADS; ++h) {
       u32x4 ra, rb;
       rotate_head(a[h], b[h], ra, rb);
-      *reinterpret_cast<u32x4*>(k_dst + h * D + off_a) = ra;
-      *reinterpret_cast<u32x4*>(k_dst + h * D + off_b) = rb;
+      st16<NT_STORE>(k_dst + h * D + off_a, ra);
+      st16<NT_STORE>(k_dst + h * D + off_b, rb);
     }
     if (v_src != nullptr) {
 #pragma unroll
       for (int h = 0; h < HEADS; ++h) {
-        a[h] = *reinterpret_cast<const u32x4*>(v_src + h * D + off_a);
-        b[h] = *reinterpret_cast<const u32x4*>(v_src + h * D + off_b);
+        a[h] = ld16<true>(v_src + h * D + off_a);
+        b[h] = ld16<true>(v_src + h * D + off_b);
       }
 #pragma unroll
       for (int h = 0; h < HEADS; ++h) {
-        *reinterpret_cast<u32x4*>(v_dst + h * D + off_a) = a[h];
-        *reinterpret_cast<u32x4*>(v_dst + h * D + off_b) = b[h];
+        st16<NT_STORE>(v_dst + h * D + off_a, a[h]);
+        st16<NT_STORE>(v_dst + h * D + off_b, b[h]);
       }
     }
   } else {
     for (int h = 0; h < n_heads; ++h) {
-      u32x4 a = *reinterpret_cast<const u32x4*>(k_src + h * D + off_a);
-      u32x4 b = *reinterpret_cast<const u32x4*>(k_src + h * D + off_b);
+      u32x4 a = ld16<true>(k_src + h * D + off_a);
+      u32x4 b = ld16<true>(k_src + h * D + off_b);
       u32x4 ra, rb;
       rotate_head(a, b, ra, rb);
-      *reinterpret_cast<u32x4*>(k_dst + h * D + off_a) = ra;
-      *reinterpret_cast<u32x4*>(k_dst + h * D + off_b) = rb;
+      st16<NT_STORE>(k_dst + h * D + off_a, ra);
+      st16<NT_STORE>(k_dst + h * D + off_b, rb);
       if (v_src != nullptr) {
-        u32x4 va = *reinterpret_cast<const u32x4*>(v_src + h * D + off_a);
-        u32x4 vb = *reinterpret_cast<const u32x4*>(v_src + h * D + off_b);
-        *reinterpret_cast<u32x4*>(v_dst + h * D + off_a) = va;
-        *reinterpret_cast<u32x4*>(v_dst + h * D + off_b) = vb;
+        u32x4 va = ld16<true>(v_src + h * D + off_a);
+        u32x4 vb = ld16<true>(v_src + h * D + off_b);
+        st16<NT_STORE>(v_dst + h * D + off_a, va);
+        st16<NT_STORE>(v_dst + h * D + off_b, vb);
       }
     }
   }
 }
 
 // Per-token positions, or one arithmetic progression of deltas (delta0 + delta_step * t).
-template <int D, int STYLE, int HEADS>
+template <int D, int STYLE, int HEADS, bool NT_STORE>
 __global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
     const uint16_t* k_src, uint16_t* k_dst, const uint16_t* v_src, uint16_t* v_dst,
     const int32_t* __restrict__ old_pos, const int32_t* __restrict__ new_pos, int32_t delta0, int32_t delta_step,
@@ -114,7 +129,7 @@ __global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
     delta = delta0 + delta_step * (int32_t)token;
   }
   const int64_t row = token * (int64_t)(HEADS > 0 ? HEADS : n_heads_rt) * D;
-  rerope_token<D, STYLE, HEADS>(k_src + row, k_dst + row, v_src ? v_src + row : nullptr,
+  rerope_token<D, STYLE, HEADS, NT_STORE>(k_src + row, k_dst + row, v_src ? v_src + row : nullptr,
                                 v_dst ? v_dst + row : nullptr, delta, jg, n_heads_rt, table);
 }
 
@@ -218,8 +233,12 @@ void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* k
       hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
                          *chunks);
   } else {
-    hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op, np, d0,
-                       dstep, n, H, t);
+    if (ks == kd)   // in place
+      hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS, true>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
+                         np, d0, dstep, n, H, t);
+    else
+      hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS, false>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
+                         np, d0, dstep, n, H, t);
   }
 }
 
