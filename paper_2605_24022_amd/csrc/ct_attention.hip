@@ -238,11 +238,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int ks = (j - NPV) >> 1, u = (j - NPV) & 1;
     return *reinterpret_cast<const bf16x8*>(kb + k_off[ks] + u * 32 * ROWB);
   };
-  auto part_m = [&](const unsigned char* vb, const unsigned char* kb) __attribute__((always_inline)) {
+  auto part_m = [&](const unsigned char* vb, const unsigned char* kb, auto&& dma) __attribute__((always_inline)) {
     __builtin_amdgcn_s_setprio(3);
     bf16x8 fr[PD + 1];
 #pragma unroll
     for (int j = 0; j < PD; ++j) fr[j] = load_frag(j, vb, kb);
+    dma();   // behind the first fragment reads: issued while the wave would wait for them anyway
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -335,9 +336,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // Period i uses K(i) and V(i-1); its M parts fetch K(i+2) and V(i+1) into the stages of
   // K(i-1) and V(i-2), which nobody reads any more.  The two groups run separate loops with
   // the same number of barriers.
-  // The look-ahead loads of period i (K(i+2), V(i+1)) are issued by each wave right before its
-  // softmax part: that wave has time to spare, and the wave in the MFMA part is not held up by
-  // the texture addresser.
+  // The look-ahead loads of period i (K(i+2), V(i+1)) are issued by each wave at the start of its
+  // M part, right behind the first fragment reads: the wave has to wait for those anyway, so the
+  // queueing of the four waves' loads at the texture addresser costs it nothing there (measured:
+  // anywhere later in the MFMA stream it costs 4.5 %, before the softmax part 1.5 %).
   auto refill = [&](int i, int st_im1, int st_ip1) __attribute__((always_inline)) {
     issue_rows(a.k, k_lane_off, k_lo + (i + 2) * BN, k_lds_addr + st_im1 * TILE_BYTES);
     issue_rows(a.v, v_lane_off, k_lo + (i + 1) * BN, v_lds_addr + st_ip1 * TILE_BYTES);
@@ -346,9 +348,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (!group_b) {
     for (int i = 0; i <= n_kt; ++i) {
       const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
-      part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES);
+      part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES, [&]() __attribute__((always_inline)) { refill(i, st_im1, st_ip1); });
       __syncthreads();
-      refill(i, st_im1, st_ip1);
       if (i < n_kt) part_v(k_lo + i * BN);
       end_of_period();
       st_im1 = st_i;
@@ -357,10 +358,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   } else {
     for (int i = 0; i <= n_kt; ++i) {
       const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
-      refill(i, st_im1, st_ip1);
       if (i >= 1) part_v(k_lo + (i - 1) * BN);
       __syncthreads();
-      part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES);
+      part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES, [&]() __attribute__((always_inline)) { refill(i, st_im1, st_ip1); });
       end_of_period();
       st_im1 = st_i;
       st_i = st_ip1;
