@@ -381,8 +381,11 @@ def main() -> int:
     if "attention" in kern:
         t_attn = (kern["attention"]["ms_per_step"] + kern.get("merge", {}).get("ms_per_step", 0.0)) * 1e-3
         ach = attn_flops / t_attn / 1e12
+        # what a kernel of nothing but MFMAs sustains on this device over ~20 ms (power-limited below the peak)
+        ceiling = B.ct_measure_mfma_rate(torch.empty(1 << 20, dtype=torch.uint8, device="cuda"), 20000, compute)
         roofline = {"bound": "mfma", "kernel": "selected attention (+ split merge)", "achieved": ach,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "measured_mfma_only_rate": ceiling, "frac_of_measured_rate": ach / ceiling,
                     "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get(sp.name),
                     "traffic_unit": "bytes per launch (HBM fetch + write)",
                     "algorithmic_flops_per_launch": attn_flops}

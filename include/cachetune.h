@@ -233,6 +233,13 @@ ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_
  * off by default, creates events on first use and is not meant for concurrent callers. */
 void ct_set_profiling(int32_t on);
 void ct_profile_reset(void);
+/* Measurement aid: the matrix-core rate this device sustains.  Runs a kernel that does nothing
+ * but dependent-free v_mfma_f32_32x32x16_bf16 (one workgroup of eight waves per compute unit,
+ * `iters` x 64 MFMAs per wave) on `stream`, waits for it, and stores the achieved TFLOP/s in
+ * *tflops (host pointer).  `scratch` is device memory of at least 256 * 512 * 4 bytes that the
+ * kernel writes its (meaningless) results to.  This is the ceiling the MFMA-bound kernels are
+ * measured against besides the published peak; it is not part of the partial-prefill path. */
+ct_status ct_measure_mfma_rate(void* scratch, int32_t iters, void* stream, double* tflops);
 ct_status ct_profile_read(int32_t kernel_class, int64_t* launches, double* total_ms);
 
 /* Message for the last non-OK status returned on this thread ("" if none). */

@@ -25,6 +25,7 @@ EXPORTS = [
     "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
     "ct_rmsnorm", "ct_linear", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
+    "ct_measure_mfma_rate",
 ]
 
 
@@ -87,6 +88,8 @@ def load() -> ctypes.CDLL:
     lib.ct_profile_reset.argtypes = []
     lib.ct_profile_reset.restype = None
     lib.ct_profile_read.argtypes = [c_int32, POINTER(c_int64), POINTER(c_double)]
+    lib.ct_measure_mfma_rate.argtypes = [c_void_p, c_int32, c_void_p, POINTER(c_double)]
+    lib.ct_measure_mfma_rate.restype = c_int32
     lib.ct_last_error.restype = c_char_p
     lib.ct_version.restype = c_char_p
     for name in ("ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
@@ -239,6 +242,13 @@ def ct_set_profiling(on: bool) -> None:
 
 def ct_profile_reset() -> None:
     load().ct_profile_reset()
+
+
+def ct_measure_mfma_rate(scratch, iters: int = 2000, stream=None) -> float:
+    """TFLOP/s of a kernel that only issues bf16 MFMAs; `scratch`: device tensor of >= 512 KiB."""
+    out = c_double(0.0)
+    _check(load().ct_measure_mfma_rate(_ptr(scratch), iters, _stream(stream), byref(out)))
+    return out.value
 
 
 def ct_profile_read(kernel_class) -> tuple:

@@ -140,6 +140,32 @@ static ct_status check_indices_host(const int32_t* idx, int32_t n_sel, int32_t n
   return CT_OK;
 }
 
+// Nothing but MFMAs on four independent accumulators per wave: the rate the matrix cores
+// sustain on this device (power-limited well below the published peak).
+__global__ __launch_bounds__(512) void mfma_rate_kernel(float* out, int iters) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    // operands that look like data (uniform in [-2, 2)): the rate is power-limited and depends on
+    // how many bits toggle - small integers run at nearly the published peak, such data does not
+    uint32_t h = (threadIdx.x * 8u + i + blockIdx.x * 4099u) * 2654435761u;
+    h ^= h >> 15;
+    a[i] = (__bf16)(((int)(h & 0xffff) - 32768) * (1.0f / 16384.0f));
+    b[i] = (__bf16)(((int)(h >> 16) - 32768) * (1.0f / 16384.0f));
+  }
+  f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+  }
+  out[blockIdx.x * 512 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
+}
+
 // Device-visible address of pinned host memory, or nullptr when `p` is not mapped for the device
 // (pageable memory, or anything the runtime does not know).
 static const void* device_view_of_host(const void* p) {
@@ -233,6 +259,33 @@ const char* ct_version(void) { return "cachetune-gfx950 0.1"; }
 void ct_set_profiling(int32_t on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
   g_prof_on = on != 0;
+}
+
+ct_status ct_measure_mfma_rate(void* scratch, int32_t iters, void* stream, double* tflops) {
+  if (scratch == nullptr || tflops == nullptr) return fail(CT_ERR_NULL, "scratch and tflops must be non-NULL");
+  if (iters <= 0 || iters > (1 << 20)) return fail(CT_ERR_SHAPE, "iters %d out of range", iters);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  hipError_t e;
+  if ((e = hipEventCreate(&e0)) != hipSuccess) return hip_fail(e, "hipEventCreate");
+  if ((e = hipEventCreate(&e1)) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return hip_fail(e, "hipEventCreate");
+  }
+  const int blocks = 256;
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(512), 0, s, static_cast<float*>(scratch), 8);   // warm-up
+  e = hipEventRecord(e0, s);
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(512), 0, s, static_cast<float*>(scratch), iters);
+  if (e == hipSuccess) e = hipEventRecord(e1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return hip_fail(e, "mfma rate measurement");
+  const double flops = (double)blocks * 8 * (double)iters * 64 * 2.0 * 32 * 32 * 16;
+  *tflops = flops / ((double)ms * 1e-3) / 1e12;
+  return CT_OK;
 }
 
 void ct_profile_reset(void) {

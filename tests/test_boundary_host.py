@@ -166,6 +166,11 @@ def test_norm_and_gemm_validation():
     B.ct_swiglu(None, 0, 512, None, None, 512, None)
 
 
+def test_mfma_rate_validation():
+    assert _status(B.ct_measure_mfma_rate, None, 100) == B.CT_ERR_NULL
+    assert _status(B.ct_measure_mfma_rate, FAKE, 0) == B.CT_ERR_SHAPE
+
+
 def _layers(n_layers=2, n_chunks=4, length=256, **kw):
     entries = []
     for _ in range(n_layers):
