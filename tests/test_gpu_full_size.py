@@ -42,3 +42,28 @@ def test_layer_config4_pinned_host_chunks_clustered_rows():
     out, kb, vb = _run_layer(wl, pinned=True)
     rows = W.sample_rows(wl.spec.n_sel, 64, seed=4)
     _check_layer(wl, out, kb, vb, rows=rows)
+
+
+def test_stack_config5_one_layer_sampled_rows():
+    """One layer of the config-5 stack at its full shape (hidden 4096, FFN 14336, 32768-token
+    context, r = 15 %, cached K/V in pinned host memory) through ct_partial_prefill_stack.  The
+    oracle computes Q, K, V of all selected rows and the whole fused cache, then attention, output
+    projection and FFN for a sample of rows (the rest of the layer is row-wise)."""
+    from oracle import ct_oracle as O
+    from tests.gpu_util import assert_close, f64_of
+    from tests.test_gpu_stack import _run_stack
+
+    sp = W.spec(5)
+    sh = sp.shape
+    sw = W.make_stack_workload(sp, n_layers=1, ffn_dim=14336)
+    h = _run_stack(sw, sw.hidden0, pinned=True)
+    lw = {k: W.bf16_bits_to_f64(v) for k, v in sw.layers[0].items()}
+    rows = W.sample_rows(sp.n_sel, 64, seed=5)
+    say(f"oracle: projections of {sp.n_sel} rows, attention and FFN of {len(rows)} sampled rows")
+    h0 = W.bf16_bits_to_f64(sw.hidden0)
+    x = O.rmsnorm(h0, lw["attn_norm"], sw.rms_eps)
+    attn, _, _, _ = O.partial_prefill_layer(x, lw["wqkv"], None, lw["k_cache"], lw["v_cache"], sw.old_pos, sw.new_pos,
+                                            sw.sel_idx, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta,
+                                            sh.rope_style, rows=rows)
+    want = O.layer_tail(h0[rows], attn, lw["wo"], lw["ffn_norm"], lw["w_gate"], lw["w_up"], lw["w_down"], sw.rms_eps)
+    assert_close(f64_of(h)[rows], want, "config-5 layer output (sampled rows)", ulp_slack=2.0 ** -8)
