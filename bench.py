@@ -239,6 +239,47 @@ def bench_stack(args, B, W, np, torch) -> int:
     ms_part, n_sel, kern_part = run(sp.ratio_pct, args.steps, args.warmup)
     log("full prefill (r=100%)")
     ms_full, _, kern_full = run(100, max(1, args.steps // 4), 1)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle on layer 0 of the same stack: projections, re-RoPE and scatter in full, attention
+        # and the row-wise rest of the layer on a sample of rows; scaled to all rows and all layers
+        log("timing the CPU oracle on one layer (sampled rows)")
+        from threadpoolctl import threadpool_info
+        from oracle import ct_oracle as O
+
+        def f64(t):
+            return W.bf16_bits_to_f64(t.cpu().view(torch.int16).numpy().view(np.uint16))
+        lw = {k: f64(v) for k, v in weights[0].items()}
+        kc, vc = f64(pools[0][0]), f64(pools[0][1])
+        spr = W.spec(5, sp.ratio_pct)
+        sel_np = W.select_indices(spr)
+        h0 = np.random.default_rng(1005).standard_normal((n_sel, E))
+        rows = W.sample_rows(n_sel, args.cpu_sample_rows, seed=1005)
+        old_pos = (np.arange(N) % sp.chunk_len).astype(np.int32)         # keys cached at chunk-local positions
+        new_pos = np.arange(N, dtype=np.int32)
+        t0 = time.perf_counter()
+        x = O.rmsnorm(h0, lw["attn_norm"], 1e-5)
+        q, k_new, v_new = O.qkv_selected(x, lw["wqkv"], None, new_pos[sel_np], sh.n_q_heads, sh.n_kv_heads, D,
+                                         sh.rope_theta, sh.rope_style)
+        k_rot = O.rerope_keys(kc, old_pos, new_pos, sh.rope_theta, sh.rope_style)
+        kf, vf = O.scatter_kv(k_rot, vc, k_new, v_new, sel_np)
+        t_full_parts = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        attn, _ = O.selected_attention(q, kf, vf, sel_np, rows=rows)
+        t_attn = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        O.layer_tail(h0[rows], attn, lw["wo"], lw["ffn_norm"], lw["w_gate"], lw["w_up"], lw["w_down"], 1e-5)
+        t_tail = time.perf_counter() - t0
+        vis_all = int((sel_np.astype(np.int64) + 1).sum())
+        vis_s = int((sel_np[rows].astype(np.int64) + 1).sum())
+        per_layer = t_full_parts + t_attn * vis_all / vis_s + t_tail * n_sel / len(rows)
+        threads = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+        cpu = {"value": per_layer * n_layers * 1e3, "unit": "ms", "cores": threads, "kind": "oracle",
+               "sample": f"fp64 NumPy oracle on layer 0: RMSNorm, QKV projection, re-RoPE, scatter in full "
+                         f"({t_full_parts:.2f}s); attention on {len(rows)} of {n_sel} rows ({t_attn:.2f}s, scaled by "
+                         f"visible keys x{vis_all / vis_s:.1f}); output projection and FFN on the same rows "
+                         f"({t_tail:.2f}s, scaled x{n_sel / len(rows):.1f}); times {n_layers} layers (extrapolated)"}
     line = {
         "metric": f"end-to-end partial prefill latency, {n_layers}-layer stack @{N // 1024}K ctx, r={sp.ratio_pct}% (vs full prefill)",
         "value": ms_part, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -251,6 +292,7 @@ def bench_stack(args, B, W, np, torch) -> int:
                   "ms_per_layer_partial": ms_part / n_layers, "ms_per_layer_full": ms_full / n_layers,
                   "host_to_device_bytes_per_layer": 2 * N * Hkv * D * 2 if args.kv_pool == "pinned" else 0,
                   "kernels_partial": kern_part, "kernels_full": kern_full},
+        "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
     return 0
