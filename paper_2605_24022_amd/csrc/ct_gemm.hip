@@ -409,7 +409,8 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
   a.Hq = cfg->n_q_heads;
   a.Hkv = cfg->n_kv_heads;
   a.O = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
-  fill_tiles(&a, false, 2);
+  const int nb = pick_nb(a, false);
+  fill_tiles(&a, false, nb);
   RopeTable rope;
   fill_rope_table(cfg, &rope);
   ChunkTable tab;
@@ -421,11 +422,18 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
     tab.row_start[1] = 0x7fffffff;
     tab.new_start[0] = 0;
   }
+  if (nb == 2) {
+    if (cfg->head_dim == 128)
+      return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0, 2>, a, rope, tab, KC_QKV, s)
+                                  : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1, 2>, a, rope, tab, KC_QKV, s);
+    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0, 2>, a, rope, tab, KC_QKV, s)
+                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1, 2>, a, rope, tab, KC_QKV, s);
+  }
   if (cfg->head_dim == 128)
-    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0, 2>, a, rope, tab, KC_QKV, s)
-                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1, 2>, a, rope, tab, KC_QKV, s);
-  return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0, 2>, a, rope, tab, KC_QKV, s)
-                              : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1, 2>, a, rope, tab, KC_QKV, s);
+    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0, 1>, a, rope, tab, KC_QKV, s)
+                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1, 1>, a, rope, tab, KC_QKV, s);
+  return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0, 1>, a, rope, tab, KC_QKV, s)
+                              : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1, 1>, a, rope, tab, KC_QKV, s);
 }
 
 ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
