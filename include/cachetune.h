@@ -135,12 +135,15 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
 
 /* One fusion-layer step of the online pipeline (Sec. 4.2; its cost model is Eq. 9):
  *   compute stream: selective recompute of q/k/v for the selected rows
- *   copy stream   : for chunks in pinned host memory, K and V rows -> k_buf / v_buf, one
- *                   event per chunk (the "Transfer stream")
- *   compute stream: per chunk, wait for its copy, re-rotate its keys into place (device
- *                   chunks are read from chunk.k / chunk.v and written to the buffers;
- *                   a device chunk whose k already points at its rows of k_buf is rotated
- *                   in place and its v is left alone)
+ *   copy stream   : chunks in pinned host memory (the "Transfer stream"): one kernel reads
+ *                   them over the host link, rotates the keys on the way (Eq. 8 overlapped with
+ *                   the transfer) and writes K and V to their rows of k_buf / v_buf; rows
+ *                   listed in sel_idx are not transferred.  Host memory the device cannot
+ *                   address is copied instead (one event per chunk) and rotated in place on
+ *                   the compute stream
+ *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
+ *                   the buffers; a device chunk whose k already points at its rows of k_buf
+ *                   is rotated in place and its v is left alone; then wait for the transfer
  *   compute stream: scatter, then selected-row attention.
  * Chunks must tile buffer rows [0, n_ctx) in order (n_ctx = sum of n_tokens) with ascending
  * new positions, so that "key position <= query position" is "key row <= query row".

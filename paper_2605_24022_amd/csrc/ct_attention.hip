@@ -13,14 +13,15 @@
 // key order (keys of a 32-key sub-tile are laid out as 16-byte units (t, lane-half) holding
 // keys 16t + 8a + 4*half + b, a in {0,1}, b in 0..3).
 //
-// Work decomposition.  A workgroup (4 waves) owns one KV head and a tile of 256 query
-// columns = (256 / G) selected tokens x the G query heads of that KV head; every wave owns
-// 64 columns and all keys.  K and V tiles of 64 keys are staged once per workgroup in LDS
-// (double buffered); V is transposed on the way in with byte permutes.  The selected rows
-// are sorted, so a tile needs keys [0, last position of the tile]; tiles past a wave's last
-// query are skipped and only tiles that straddle a query position evaluate the causal mask.
+// Work decomposition.  A workgroup (8 waves, two per SIMD) owns one KV head and a tile of 256
+// query columns = (256 / G) selected tokens x the G query heads of that KV head; every wave
+// owns 32 columns and all keys.  K and V tiles of 64 keys are staged once per workgroup in LDS
+// by direct global->LDS loads (three stages each); V^T fragments come out of LDS with
+// transposing reads.  The selected rows are sorted, so a tile needs keys [0, last position of
+// the tile]; only key tiles that straddle a query position of the wave evaluate the causal mask.
 // When (tile, head) pairs are too few to fill the chip, the key range is split and fp32
-// partial (O, m, l) are merged by a second kernel.
+// partial (O, m, l) are merged by a second kernel; tiles whose keys fit one split write their
+// result directly.
 // Workgroup ids map KV head = id mod n_kv_heads, so with 8 KV heads every XCD streams the
 // keys of one head through its own L2; tiles are issued heaviest first.
 #include <math.h>
