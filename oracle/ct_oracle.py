@@ -18,7 +18,7 @@ intermediate rounding:
                       raw pre-RoPE cache is the special case old_pos = 0.
   scatter_kv          scatter fusion (Sec. 4.2, "Reducing online recomputation and fusion
                       overhead"): recomputed rows overwrite their slots of the layer buffer.
-  selected_attention  the check/fusion-layer attention "only for the corresponding tokens":
+  selected_attention  the check/fusion-layer attention, computed for the selected tokens alone:
                       causal softmax attention of the selected queries over the fused KV.
   partial_prefill_layer  the composition of the four.
   rmsnorm, swiglu_ffn, layer_tail, partial_prefill_stack

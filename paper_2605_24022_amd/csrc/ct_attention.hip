@@ -1,5 +1,5 @@
 // Causal attention for the selected query rows over the fused layer KV (Sec. 4.2: the
-// check / fusion layers compute attention "only for the corresponding tokens"), GQA aware.
+// check / fusion layers compute attention for the selected tokens alone), GQA aware.
 //
 // Formulation.  Everything is computed transposed so that a lane owns a query column:
 //   S^T = K Q^T            A = K tile rows (keys) from LDS,       B = Q^T kept in registers
