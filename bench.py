@@ -176,7 +176,7 @@ def bench_stack(args, B, W, np, torch) -> int:
         weights.append(dict(attn_norm=ones, wqkv=rnd((sh.qkv_width, E), E ** -0.5), wo=rnd((E, qd), qd ** -0.5),
                             ffn_norm=ones, w_gate=rnd((ffn, E), E ** -0.5), w_up=rnd((ffn, E), E ** -0.5),
                             w_down=rnd((E, ffn), ffn ** -0.5)))
-        if args.kv_pool == "pinned":
+        if args.kv_pool in ("pinned", "compact"):
             kp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
             vp = torch.empty((N, Hkv, D), dtype=torch.bfloat16, pin_memory=True)
             kp.copy_(rnd((N, Hkv, D), 1.0))
@@ -192,10 +192,30 @@ def bench_stack(args, B, W, np, torch) -> int:
         n_sel = sel_np.size
         sel = torch.from_numpy(sel_np).cuda()
         entries, keep = [], []
+        compact = args.kv_pool == "compact" and ratio_pct < 100
+        if compact:   # per chunk: the rows that are not recomputed, gathered into a pool of their own
+            kept = [torch.from_numpy(np.setdiff1d(np.arange(c * sp.chunk_len, (c + 1) * sp.chunk_len), sel_np))
+                    for c in range(sp.n_chunks)]
         for lw, (kp, vp) in zip(weights, pools):
+            if compact:
+                parts = []
+                for c in range(sp.n_chunks):
+                    kc = torch.empty((len(kept[c]), Hkv, D), dtype=torch.bfloat16, pin_memory=True)
+                    vc = torch.empty_like(kc).pin_memory()
+                    kc.copy_(kp[kept[c]])
+                    vc.copy_(vp[kept[c]])
+                    parts.append((kc, vc))
+                keep.append(parts)
+                ch = B.make_chunks([dict(k=parts[c][0], v=parts[c][1], n_tokens=sp.chunk_len, old_pos_start=0,
+                                         new_pos_start=c * sp.chunk_len, location=2) for c in range(sp.n_chunks)])
+                keep.append(ch)
+                d = dict(lw)
+                d["chunks"] = ch
+                entries.append(d)
+                continue
             ch = B.make_chunks([dict(k=kp[c * sp.chunk_len:(c + 1) * sp.chunk_len], v=vp[c * sp.chunk_len:(c + 1) * sp.chunk_len],
                                      n_tokens=sp.chunk_len, old_pos_start=0, new_pos_start=c * sp.chunk_len,
-                                     location=1 if args.kv_pool == "pinned" else 0)
+                                     location=0 if args.kv_pool == "device" else 1)
                                 for c in range(sp.n_chunks)])
             keep.append(ch)
             d = dict(lw)
@@ -286,11 +306,12 @@ def bench_stack(args, B, W, np, torch) -> int:
         "ms_per_step": ms_part, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": sp.name, "layers": n_layers, "n_ctx": N, "n_sel": n_sel, "ffn_dim": ffn,
-                   "kv_pool": "pinned host, streamed one layer ahead on a second stream" if args.kv_pool == "pinned"
-                   else "device-resident"},
+                   "kv_pool": {"pinned": "pinned host, streamed one layer ahead on a second stream",
+                               "compact": "pinned host holding only the rows that are not recomputed, streamed one layer ahead",
+                               "device": "device-resident"}[args.kv_pool]},
         "extra": {"full_prefill_ms": ms_full, "speedup_vs_full_prefill": ms_full / ms_part,
                   "ms_per_layer_partial": ms_part / n_layers, "ms_per_layer_full": ms_full / n_layers,
-                  "host_to_device_bytes_per_layer": 2 * N * Hkv * D * 2 if args.kv_pool == "pinned" else 0,
+                  "host_to_device_bytes_per_layer": 0 if args.kv_pool == "device" else 2 * (N - n_sel) * Hkv * D * 2,
                   "kernels_partial": kern_part, "kernels_full": kern_full},
         "cpu_baseline": cpu,
     }
@@ -305,8 +326,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: number of layers")
-    ap.add_argument("--kv-pool", choices=["pinned", "device"], default="pinned",
-                    help="config 5 only: where the per-layer cached K/V live (pinned host memory is the paper's CPU pool)")
+    ap.add_argument("--kv-pool", choices=["pinned", "compact", "device"], default="pinned",
+                    help="config 5 only: where the per-layer cached K/V live (pinned host memory is the paper's CPU pool; "
+                         "compact = pinned, holding only the rows that are not recomputed)")
     ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=96)

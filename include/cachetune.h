@@ -60,7 +60,10 @@ typedef struct {
 
 /* One reusable KV chunk (the paper's unit of storage and transfer, Sec. 3 and 4.2).
  * k, v: bf16 [n_tokens, n_kv_heads, head_dim], device memory (location 0) or pinned host
- * memory (location 1).  In the new context token t of the chunk sits at position
+ * memory (location 1).  Location 2 is a pool that dropped the recompute set when the chunk was
+ * offloaded (Sec. 4.2, index-aware offloading): pinned host memory holding, in order, only the
+ * chunk's rows that are NOT in sel_idx - n_tokens minus the number of selected rows of the
+ * chunk; n_tokens still counts all tokens of the chunk.  In the new context token t of the chunk sits at position
  * new_pos_start + t.  raw_keys = 0: the keys were cached after RoPE at positions
  * old_pos_start + t and are rotated by new_pos_start - old_pos_start.  raw_keys = 1: the
  * keys were cached before RoPE (the paper's own scheme, Eq. 8) and token t is rotated by

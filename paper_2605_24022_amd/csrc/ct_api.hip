@@ -203,10 +203,14 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
   const void* kview[64];
   const void* vview[64];
   for (int c = 0; c < n_chunks; ++c) {
-    if (chunks[c].location != 1) continue;
+    if (chunks[c].location == 0) continue;
     kview[c] = device_view_of_host(chunks[c].k);
     vview[c] = device_view_of_host(chunks[c].v);
-    if (kview[c] == nullptr || vview[c] == nullptr) return CT_OK;   // caller falls back to copies
+    if (kview[c] == nullptr || vview[c] == nullptr) {
+      if (chunks[c].location == 2)
+        return fail(CT_ERR_UNSUPPORTED, "chunk %d: a compact pool must be in pinned host memory the device can address", c);
+      return CT_OK;   // caller falls back to copies
+    }
   }
   ReropeChunks rc;
   memset(&rc, 0, sizeof(rc));
@@ -217,17 +221,19 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
   auto flush = [&]() -> ct_status {
     if (rc.n == 0) return CT_OK;
     rc.tok_start[rc.n] = rc.total_tokens;
-    rc.skip_rows = skip_selected && n_sel > 0 ? sel_idx : nullptr;
+    rc.skip_rows = (skip_selected || rc.compact_mask != 0) && n_sel > 0 ? sel_idx : nullptr;
     rc.n_skip = n_sel;
     ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, stream_in_blocks(), xs);
     rc.n = 0;
     rc.total_tokens = 0;
+    rc.compact_mask = 0;
     return r;
   };
   for (int c = 0; c < n_chunks; ++c) {
     const ct_chunk& ch = chunks[c];
-    if (ch.location != 1) continue;
+    if (ch.location == 0) continue;
     const int i = rc.n++;
+    if (ch.location == 2) rc.compact_mask |= 1u << i;
     rc.tok_start[i] = rc.total_tokens;
     rc.total_tokens += ch.n_tokens;
     rc.k_src[i] = kview[c];
@@ -420,12 +426,12 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   memset(&tab, 0, sizeof(tab));
   tab.n = n_chunks;
   int64_t n_ctx64 = 0;
-  bool any_host = false;
+  bool any_host = false, any_compact = false;
   for (int c = 0; c < n_chunks; ++c) {
     const ct_chunk& ch = chunks[c];
     if (ch.n_tokens <= 0) return fail(CT_ERR_SHAPE, "chunk %d has n_tokens %d", c, ch.n_tokens);
     if (ch.k == nullptr || ch.v == nullptr) return fail(CT_ERR_NULL, "chunk %d has a NULL k or v", c);
-    if (ch.location != 0 && ch.location != 1) return fail(CT_ERR_SHAPE, "chunk %d has location %d", c, ch.location);
+    if (ch.location < 0 || ch.location > 2) return fail(CT_ERR_SHAPE, "chunk %d has location %d", c, ch.location);
     if (ch.new_pos_start < 0) return fail(CT_ERR_SHAPE, "chunk %d has negative new_pos_start", c);
     if (c > 0) {
       const ct_chunk& pr = chunks[c - 1];
@@ -433,7 +439,8 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
         return fail(CT_ERR_SHAPE, "chunk %d starts at position %d, before chunk %d ends (%lld)", c, ch.new_pos_start,
                     c - 1, (long long)pr.new_pos_start + pr.n_tokens);
     }
-    any_host |= ch.location == 1;
+    any_host |= ch.location != 0;
+    any_compact |= ch.location == 2;
     tab.row_start[c] = (int32_t)n_ctx64;
     tab.new_start[c] = ch.new_pos_start;
     n_ctx64 += ch.n_tokens;
@@ -499,6 +506,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     // rotates the keys on the way and writes keys and values to their buffer rows (Eq. 8 overlapped
     // with the transfer); one event says that all of them are in place.
     if ((st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, sel_idx, n_sel, xs, &streamed)) != CT_OK) return st;
+    if (!streamed && any_compact) return fail(CT_ERR_UNSUPPORTED, "compact pools are read by the stream-in kernel only");
     landed.resize(n_chunks, nullptr);
     if (streamed) {
       e = hipEventCreateWithFlags(&landed[0], hipEventDisableTiming);

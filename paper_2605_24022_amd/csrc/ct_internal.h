@@ -54,6 +54,7 @@ struct ReropeChunks {
   int32_t delta_step[32];
   const int32_t* skip_rows;   // optional: sorted buffer rows that are not to be brought in (device memory)
   int32_t n_skip;
+  uint32_t compact_mask;      // bit c: the source of chunk c holds only its rows that are not in skip_rows
 };
 // LDS that the small kernels of the recompute stream claim without using it (the large ones need
 // at least as much anyway): together with the 80 KiB the stream-in kernel claims, it keeps the two

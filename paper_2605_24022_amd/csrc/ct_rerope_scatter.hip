@@ -145,17 +145,24 @@ __device__ __forceinline__ void rerope_chunk_tokens(uint16_t* k_buf, uint16_t* v
     int c = 0;
     while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
     const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
+    int32_t t_src = t;   // row inside the chunk's source
     if (chunks.skip_rows != nullptr) {   // binary search for this buffer row in the sorted skip list
+      auto below = [&](int32_t row) {   // number of skipped rows < row
+        int lo = 0, hi = chunks.n_skip;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (chunks.skip_rows[mid] < row) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+      };
       const int32_t row = chunks.row_start[c] + t;
-      int lo = 0, hi = chunks.n_skip;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (chunks.skip_rows[mid] < row) lo = mid + 1; else hi = mid;
-      }
+      const int lo = below(row);
       if (lo < chunks.n_skip && chunks.skip_rows[lo] == row) continue;
+      // a compact source holds only the rows that are kept: step over the skipped ones before this row
+      if ((chunks.compact_mask >> c) & 1u) t_src = t - (lo - below(chunks.row_start[c]));
     }
     const int64_t heads = HEADS > 0 ? HEADS : n_heads_rt;
-    const int64_t src_row = (int64_t)t * heads * D;
+    const int64_t src_row = (int64_t)t_src * heads * D;
     const int64_t dst_row = ((int64_t)chunks.row_start[c] + t) * heads * D;
     const uint16_t* ks = static_cast<const uint16_t*>(chunks.k_src[c]) + src_row;
     const uint16_t* vs = chunks.v_src[c] ? static_cast<const uint16_t*>(chunks.v_src[c]) + src_row : nullptr;

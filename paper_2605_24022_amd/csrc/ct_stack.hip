@@ -180,7 +180,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
   memset(&tab, 0, sizeof(tab));
   tab.n = n_chunks;
   int64_t n_ctx64 = 0;
-  bool any_host = false;
+  bool any_host = false, any_compact = false;
   for (int l = 0; l < n_layers; ++l) {
     const ct_layer_weights& lw = layers[l];
     if (!lw.attn_norm || !lw.wqkv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
@@ -190,7 +190,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     for (int c = 0; c < n_chunks; ++c) {
       const ct_chunk& ch = lw.chunks[c];
       if (ch.n_tokens <= 0) return fail(CT_ERR_SHAPE, "layer %d chunk %d has n_tokens %d", l, c, ch.n_tokens);
-      if (ch.location != 0 && ch.location != 1) return fail(CT_ERR_SHAPE, "layer %d chunk %d has location %d", l, c, ch.location);
+      if (ch.location < 0 || ch.location > 2) return fail(CT_ERR_SHAPE, "layer %d chunk %d has location %d", l, c, ch.location);
       if (ch.new_pos_start < 0) return fail(CT_ERR_SHAPE, "layer %d chunk %d has negative new_pos_start", l, c);
       if (l == 0) {
         if (c > 0 && (int64_t)ch.new_pos_start < (int64_t)lw.chunks[c - 1].new_pos_start + lw.chunks[c - 1].n_tokens)
@@ -200,7 +200,8 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
       } else if (ch.n_tokens != layers[0].chunks[c].n_tokens || ch.new_pos_start != layers[0].chunks[c].new_pos_start) {
         return fail(CT_ERR_SHAPE, "layer %d chunk %d differs in geometry from layer 0", l, c);
       }
-      any_host |= ch.location == 1;
+      any_host |= ch.location != 0;
+      any_compact |= ch.location == 2;
       rows += ch.n_tokens;
       if (rows > 0x7fffffff / 2) return fail(CT_ERR_SHAPE, "context too long");
     }
@@ -270,6 +271,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     ct_status sst = stream_in_host_chunks(cfg, layers[l].chunks, n_chunks, tab, kb, vb, sel_idx, n_sel, xs, &done);
     if (sst != CT_OK) return sst;
     streamed[l & 1] = done;
+    if (!done && any_compact) return fail(CT_ERR_UNSUPPORTED, "compact pools are read by the stream-in kernel only");
     if (done) {
       if ((e = hipEventRecord(landed(l, 0), xs)) != hipSuccess) return hip_fail(e, "hipEventRecord (chunks streamed in)");
       return CT_OK;

@@ -120,6 +120,8 @@ def test_layer_validation():
     assert call(chunks=bad) == B.CT_ERR_SHAPE
     bad = _chunks(); bad[3].k = None
     assert call(chunks=bad) == B.CT_ERR_NULL
+    bad = _chunks(); bad[0].location = 3
+    assert call(chunks=bad) == B.CT_ERR_SHAPE
     host = _chunks(location=1)                               # pinned-host chunks need a second stream
     need = B.ct_workspace_bytes(c, 1024, 153)
     assert call(chunks=host, workspace=FAKE, workspace_bytes=need) == B.CT_ERR_SHAPE

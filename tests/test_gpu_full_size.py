@@ -44,6 +44,13 @@ def test_layer_config4_pinned_host_chunks_clustered_rows():
     _check_layer(wl, out, kb, vb, rows=rows)
 
 
+def test_layer_config2_compact_host_pool():
+    """8192-token context, forced + uniform rows; the host pool holds only the rows that are reused."""
+    wl = W.make_workload(W.spec(2))
+    out, kb, vb = _run_layer(wl, compact=True)
+    _check_layer(wl, out, kb, vb)
+
+
 def test_stack_config5_one_layer_sampled_rows():
     """One layer of the config-5 stack at its full shape (hidden 4096, FFN 14336, 32768-token
     context, r = 15 %, cached K/V in pinned host memory) through ct_partial_prefill_stack.  The

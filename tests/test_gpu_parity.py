@@ -188,7 +188,7 @@ def test_selected_attention_clustered_rows():
 
 
 # ------------------------------------------------------------------------------ whole layer
-def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False):
+def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False):
     sp, sh = wl.spec, wl.spec.shape
     cfg = B.cfg_from_shape(sh)
     n_ctx, n_sel = sp.n_ctx, sp.n_sel
@@ -214,9 +214,16 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False):
         k_pool, v_pool = k_buf, v_buf
     else:
         k_pool, v_pool = dev_bf16(k_cache), dev_bf16(v_cache)
-    entries = []
+    entries, keep_alive = [], []
     for c in range(sp.n_chunks):
         lo, hi = int(wl.chunk_rows[c]), int(wl.chunk_rows[c + 1])
+        if compact:   # the pool dropped the recompute set: only the other rows of the chunk, in order
+            kept = np.setdiff1d(np.arange(lo, hi), wl.sel_idx)
+            kc, vc = pinned_bf16(k_cache[kept]), pinned_bf16(v_cache[kept])
+            keep_alive.append((kc, vc))
+            entries.append(dict(k=kc, v=vc, n_tokens=hi - lo, old_pos_start=int(wl.chunk_old_start[c]),
+                                new_pos_start=int(wl.chunk_new_start[c]), location=2))
+            continue
         entries.append(dict(k=k_pool[lo:hi], v=v_pool[lo:hi], n_tokens=hi - lo,
                             old_pos_start=int(wl.chunk_old_start[c]), new_pos_start=int(wl.chunk_new_start[c]),
                             location=1 if pinned else 0))
@@ -253,11 +260,11 @@ def _check_layer(wl, out, k_buf, v_buf, rows=None):
     assert_close(f64_of(v_buf)[wl.sel_idx], v_want[wl.sel_idx], f"{wl.spec.name} recomputed V")
 
 
-@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned", "pageable"])
+@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned", "pageable", "compact"])
 def test_layer_config1(mode):
     wl = W.make_workload(W.spec(1))
     out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place",
-                             pageable=mode == "pageable")
+                             pageable=mode == "pageable", compact=mode == "compact")
     _check_layer(wl, out, kb, vb)
 
 
