@@ -226,6 +226,33 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
                                    size_t workspace_bytes, void* compute_stream, void* copy_stream);
 size_t ct_stack_workspace_bytes(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx, int32_t n_sel);
 
+/* ---- Choice of the recomputation ratio for a given GPU and cache pool (Sec. 4.3).  Host code. ---- */
+
+/* Per-layer latency model, Eq. 9: max(r N t_c, (1 - r) N t_i) + t_o.  t_c: recomputation cost
+ * per token and layer, t_i: transfer cost per token and layer, t_o: fixed cost per layer (all
+ * in the same unit of time; the result is in that unit).  Multiply by the number of layers for
+ * the steady-state TTFT of Eq. 10. */
+double ct_layer_latency_model(double r, double n_tokens, double t_c, double t_i, double t_o);
+
+/* Crossover of the two branches of Eq. 9 (Eq. 11): t_i / (t_c + t_i), clipped to
+ * [r_min, r_max] (r_min is the quality floor of Sec. 4.3, 0.15 in the paper). */
+double ct_ratio_prior(double t_c, double t_i, double r_min, double r_max);
+
+/* Golden-section search for the ratio with the least measured latency (Alg. 1), warm-started at
+ * the prior r0: `eval(r, user)` returns the mean TTFT of the calibration set at ratio r and is
+ * called once per iteration after the first two probes.  Stops when the bracket is narrower than
+ * eps or after max_evals evaluations; *r_star is the midpoint of the final bracket, *n_evals
+ * (may be NULL) the number of evaluations made.  Two departures from the listing, both needed
+ * because r0 is not at a golden point of [r_min, r_max]: each new probe is the golden-section
+ * point of the larger part that the surviving probe leaves of the bracket (the listing's
+ * expression whenever the survivor is at a golden point; off it the listing's point can meet or
+ * pass the survivor and the minimum is lost), and a prior that sits on a bound is moved inside
+ * by a hundredth of the interval.  Errors: CT_ERR_NULL (eval, r_star), CT_ERR_RATIO (bounds not
+ * 0 <= r_min <= r_max <= 1), CT_ERR_SHAPE (eps <= 0, max_evals < 2). */
+typedef double (*ct_ttft_fn)(double r, void* user);
+ct_status ct_ratio_search(ct_ttft_fn eval, void* user, double r0, double r_min, double r_max, double eps,
+                          int32_t max_evals, double* r_star, int32_t* n_evals);
+
 /* Host-side check of an index set: strictly ascending and inside [0, n_ctx). */
 ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_ctx);
 

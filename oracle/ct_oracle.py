@@ -28,6 +28,12 @@ intermediate rounding:
                       the models (Sec. 5) but not these formulas; they are the standard RMSNorm
                       and SwiGLU definitions of those models.
 
+  layer_latency_model, ratio_prior, ratio_search
+                      the hardware-aware choice of the recomputation ratio (Sec. 4.3): the
+                      latency model of Eq. 9, its crossover (Eq. 11) and the warm-started
+                      golden-section search of Alg. 1.  The search is an iteration, so it is
+                      written step by step in the algorithm's notation.
+
 Readings where the paper is silent (RoPE pair convention and frequencies, softmax scale,
 GQA head mapping, floor for r*N, V being position independent) are stated at the function
 that uses them.  All pins live in tests/test_oracle_pins.py.
@@ -239,3 +245,63 @@ def partial_prefill_stack(h_sel, layers, old_pos, new_pos, sel_idx, n_q_heads, n
             inputs.append(h)
         h, _, _ = transformer_layer(h, lw, old_pos, new_pos, sel_idx, n_q_heads, n_kv_heads, head_dim, theta, eps, style)
     return (h, inputs) if keep_inputs else h
+
+
+# ----------------------------------------------------------------------------- ratio scheduling (Sec. 4.3)
+def layer_latency_model(r, n_tokens, t_c, t_i, t_o):
+    """Eq. 9: recomputation of r N tokens overlaps the transfer of the other (1 - r) N; the
+    slower of the two plus the fixed per-layer cost is the layer's latency."""
+    return max(r * n_tokens * t_c, (1.0 - r) * n_tokens * t_i) + t_o
+
+
+def ratio_prior(t_c, t_i, r_min, r_max):
+    """Eq. 11, clipped to the semantic bounds as Alg. 1 requires of its input."""
+    r0 = t_i / (t_c + t_i) if (t_c + t_i) > 0.0 else r_min
+    return min(max(r0, r_min), r_max)
+
+
+def ratio_search(f, r0, r_min, r_max, eps, max_evals=64):
+    """Alg. 1: golden-section search on [r_min, r_max] with the prior r0 as one of the first two
+    probes.  Returns (r_star, probes), probes being the ratios f was evaluated at, in order.
+
+    Readings.  (1) The listing places each new probe at b - phi (b - a) or a + phi (b - a) and
+    makes the surviving probe the other one.  That is right when the survivor sits at a golden
+    point of the shrunken bracket, which textbook starting probes guarantee and r0 does not: with
+    an off-golden survivor the new probe can coincide with it or land on its wrong side, and the
+    next comparison then discards the part of the bracket that holds the minimum.  Here the new
+    probe is the golden-section point of the larger of the two parts into which the survivor
+    splits the bracket (the usual golden step of bracketing minimisers); it equals the listing's
+    expression whenever the survivor is at a golden point, and keeps a < x1 < x2 < b always.
+    (2) An r0 that was clipped onto a bound is moved inside by 1 % of the bracket: a probe at the
+    bound cannot tell the search which side the minimum is on.  (3) max_evals bounds the loop,
+    since f is a noisy measurement in practice."""
+    a, b = float(r_min), float(r_max)
+    r0 = min(max(float(r0), a), b)
+    phi = (np.sqrt(5.0) - 1.0) / 2.0
+    probes = []
+
+    def evaluate(x):
+        probes.append(x)
+        return f(x)
+
+    if b - a < eps:
+        return (a + b) / 2.0, probes
+    inset = 0.01 * (b - a)
+    if r0 <= (a + b) / 2.0:
+        x1, x2 = max(r0, a + inset), a + phi * (b - a)
+    else:
+        x1, x2 = b - phi * (b - a), min(r0, b - inset)
+    f1 = evaluate(x1)
+    f2 = evaluate(x2)
+    while abs(b - a) >= eps and len(probes) < max_evals:
+        if f1 < f2:          # the minimum lies in [a, x2]; x1 survives
+            b, s, fs = x2, x1, f1
+        else:                # the minimum lies in [x1, b]; x2 survives
+            a, s, fs = x1, x2, f2
+        if s - a > b - s:    # new probe left of the survivor
+            x1, x2, f2 = s - (1.0 - phi) * (s - a), s, fs
+            f1 = evaluate(x1)
+        else:                # new probe right of the survivor
+            x1, x2, f1 = s, s + (1.0 - phi) * (b - s), fs
+            f2 = evaluate(x2)
+    return (a + b) / 2.0, probes

@@ -25,8 +25,11 @@ EXPORTS = [
     "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
     "ct_rmsnorm", "ct_linear", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
-    "ct_measure_mfma_rate",
+    "ct_measure_mfma_rate", "ct_layer_latency_model", "ct_ratio_prior", "ct_ratio_search",
 ]
+
+
+TTFT_FN = ctypes.CFUNCTYPE(c_double, c_double, c_void_p)
 
 
 class LayerCfg(ctypes.Structure):
@@ -88,6 +91,13 @@ def load() -> ctypes.CDLL:
     lib.ct_profile_reset.argtypes = []
     lib.ct_profile_reset.restype = None
     lib.ct_profile_read.argtypes = [c_int32, POINTER(c_int64), POINTER(c_double)]
+    lib.ct_layer_latency_model.argtypes = [c_double] * 5
+    lib.ct_layer_latency_model.restype = c_double
+    lib.ct_ratio_prior.argtypes = [c_double] * 4
+    lib.ct_ratio_prior.restype = c_double
+    lib.ct_ratio_search.argtypes = [TTFT_FN, c_void_p, c_double, c_double, c_double, c_double, c_int32,
+                                    POINTER(c_double), POINTER(c_int32)]
+    lib.ct_ratio_search.restype = c_int32
     lib.ct_measure_mfma_rate.argtypes = [c_void_p, c_int32, c_void_p, POINTER(c_double)]
     lib.ct_measure_mfma_rate.restype = c_int32
     lib.ct_last_error.restype = c_char_p
@@ -242,6 +252,22 @@ def ct_set_profiling(on: bool) -> None:
 
 def ct_profile_reset() -> None:
     load().ct_profile_reset()
+
+
+def ct_layer_latency_model(r, n_tokens, t_c, t_i, t_o) -> float:
+    return float(load().ct_layer_latency_model(r, n_tokens, t_c, t_i, t_o))
+
+
+def ct_ratio_prior(t_c, t_i, r_min, r_max) -> float:
+    return float(load().ct_ratio_prior(t_c, t_i, r_min, r_max))
+
+
+def ct_ratio_search(eval_fn, r0, r_min, r_max, eps, max_evals=64):
+    """eval_fn(r) -> latency.  Returns (r_star, number of evaluations)."""
+    cb = TTFT_FN(lambda r, _user: float(eval_fn(r)))
+    out, n = c_double(0.0), c_int32(0)
+    _check(load().ct_ratio_search(cb, None, r0, r_min, r_max, eps, max_evals, byref(out), byref(n)))
+    return out.value, n.value
 
 
 def ct_measure_mfma_rate(scratch, iters: int = 2000, stream=None) -> float:

@@ -416,3 +416,84 @@ def test_stack_partial_first_selected_row_is_a_closed_chain():
         h = h + O.swiglu_ffn(O.rmsnorm(h[None], lw["ffn_norm"], eps), lw["w_gate"], lw["w_up"], lw["w_down"])[0]
     np.testing.assert_allclose(got[0], h, atol=1e-10)
     assert len(inputs) == 2 and np.array_equal(inputs[0], h0)
+
+
+# ----------------------------------------------------------------------------- ratio scheduling (Sec. 4.3)
+def test_latency_model_end_points_and_crossover():
+    """Eq. 9 against what it must give at the ends and at the crossover of Eq. 11: all-transfer at
+    r = 0, all-compute at r = 1, both branches equal at r0, and r0 is where a brute-force scan of
+    the model finds its minimum."""
+    N, t_c, t_i, t_o = 32768, 0.7e-3, 0.09e-3, 0.05
+    assert O.layer_latency_model(0.0, N, t_c, t_i, t_o) == pytest.approx(N * t_i + t_o, rel=1e-15)
+    assert O.layer_latency_model(1.0, N, t_c, t_i, t_o) == pytest.approx(N * t_c + t_o, rel=1e-15)
+    r0 = O.ratio_prior(t_c, t_i, 0.0, 1.0)
+    assert r0 * N * t_c == pytest.approx((1 - r0) * N * t_i, rel=1e-12)
+    assert r0 == pytest.approx(0.09 / 0.79, rel=1e-12)          # 9/79 by hand
+    grid = np.linspace(0.0, 1.0, 100001)
+    vals = [O.layer_latency_model(r, N, t_c, t_i, t_o) for r in grid]
+    assert abs(grid[int(np.argmin(vals))] - r0) <= 1e-5
+    # left of the crossover the transfer term decides, right of it the compute term
+    assert O.layer_latency_model(0.05, N, t_c, t_i, t_o) == pytest.approx(0.95 * N * t_i + t_o)
+    assert O.layer_latency_model(0.5, N, t_c, t_i, t_o) == pytest.approx(0.5 * N * t_c + t_o)
+    # the clip
+    assert O.ratio_prior(t_c, t_i, 0.15, 0.6) == 0.15
+    assert O.ratio_prior(t_i, t_c, 0.15, 0.6) == 0.6
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_ratio_search_finds_the_minimum_of_unimodal_functions(seed):
+    """Alg. 1 against the definition of what it looks for: on unimodal functions with a known
+    minimiser (inside the bracket, on either bound, at the prior, far from the prior) the result
+    is within eps/2 of it, every probe lies inside the bracket, and the bracket argument holds
+    for smooth and kinked shapes alike.  A brute-force scan gives the minimiser of the Eq. 9
+    model itself."""
+    rng = np.random.default_rng(seed)
+    r_min, r_max, eps = 0.15, 0.9, 1e-3
+    cases = []
+    for _ in range(20):
+        m = rng.uniform(r_min, r_max)
+        cases.append((lambda r, m=m: (r - m) ** 2, m))
+        cases.append((lambda r, m=m: abs(r - m) ** 0.5, m))
+        cases.append((lambda r, m=m: (m - r) * 3.0 if r < m else (r - m) * 0.2, m))     # lopsided V
+    cases.append((lambda r: r, r_min))           # increasing: minimum on the lower bound
+    cases.append((lambda r: -r, r_max))          # decreasing: on the upper bound
+    t_c, t_i = 0.2e-3, 0.5e-3
+    cases.append((lambda r: O.layer_latency_model(r, 4096, t_c, t_i, 0.3), 5.0 / 7.0))
+    for f, m in cases:
+        for r0 in (r_min, r_max, m, rng.uniform(r_min, r_max), 0.5 * (r_min + r_max)):
+            r_star, probes = O.ratio_search(f, r0, r_min, r_max, eps)
+            assert abs(r_star - m) <= eps / 2 + 1e-12, (m, r0, r_star)
+            assert all(r_min < x < r_max for x in probes)
+            assert len(probes) <= 18       # the textbook count for this bracket and eps is 16
+            grid = np.linspace(r_min, r_max, 7501)
+            brute = grid[int(np.argmin([f(x) for x in grid]))]
+            assert abs(r_star - brute) <= eps / 2 + 1e-4 + 1e-12
+
+
+def test_ratio_search_reduces_to_textbook_golden_section():
+    """With the prior exactly at the lower golden point the warm start changes nothing and the
+    search is the textbook one: every iteration shrinks the bracket by (sqrt(5)-1)/2, so the
+    number of evaluations is 2 + ceil(log(eps / width) / log(phi)), and the result agrees with
+    SciPy's golden-section routine."""
+    from scipy.optimize import golden
+    phi = (math.sqrt(5.0) - 1.0) / 2.0
+    a, b = 0.15, 0.9
+    f = lambda r: (r - 0.4321) ** 2 + 1.0
+    for eps in (1e-1, 1e-2, 1e-3, 1e-5):
+        r_star, probes = O.ratio_search(f, b - phi * (b - a), a, b, eps)
+        assert len(probes) == 2 + math.ceil(math.log(eps / (b - a)) / math.log(phi))
+        # consecutive brackets nest with ratio phi: the probes are all golden points
+        assert abs(r_star - 0.4321) <= eps / 2
+    lib = golden(f, brack=(a, b), tol=1e-10)
+    r_star, _ = O.ratio_search(f, b - phi * (b - a), a, b, 1e-7)
+    assert abs(r_star - lib) <= 1e-6
+
+
+def test_ratio_search_degenerate_brackets():
+    calls = []
+    f = lambda r: calls.append(r) or r * r
+    assert O.ratio_search(f, 0.3, 0.3, 0.3, 1e-3) == (0.3, [])
+    r_star, probes = O.ratio_search(f, 0.2, 0.2, 0.2004, 1e-3)
+    assert r_star == pytest.approx(0.2002) and probes == [] and calls == []
+    r_star, probes = O.ratio_search(f, 0.5, 0.1, 0.9, 1e-6, max_evals=5)
+    assert len(probes) == 5 and 0.1 < r_star < 0.9
