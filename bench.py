@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -186,17 +187,22 @@ def bench_stack(args, B, W, np, torch) -> int:
         pools.append((kp, vp))
     torch.cuda.synchronize()
 
-    def run(ratio_pct, steps, warmup):
-        spr = W.spec(5, ratio_pct) if ratio_pct < 100 else W.custom_spec("cfg5-full", sh, sp.n_chunks, sp.chunk_len, 100, "all", 1005)
-        sel_np = W.select_indices(spr)
-        n_sel = sel_np.size
+    dev_pools = []
+
+    def run(r, steps, warmup, kv_pool=args.kv_pool):
+        """Mean latency of the stack at recompute ratio r (a fraction; floor(r N) rows)."""
+        n_sel = N if r >= 1.0 else max(1, int(math.floor(r * N + 1e-9)))
+        sel_np = W.select_indices(sp, n_sel)
         sel = torch.from_numpy(sel_np).cuda()
         entries, keep = [], []
-        compact = args.kv_pool == "compact" and ratio_pct < 100
+        compact = kv_pool == "compact" and r < 1.0
+        if kv_pool == "device" and args.kv_pool != "device" and not dev_pools:
+            dev_pools.extend((kp.cuda(), vp.cuda()) for kp, vp in pools)
+        use_pools = dev_pools if (kv_pool == "device" and args.kv_pool != "device") else pools
         if compact:   # per chunk: the rows that are not recomputed, gathered into a pool of their own
             kept = [torch.from_numpy(np.setdiff1d(np.arange(c * sp.chunk_len, (c + 1) * sp.chunk_len), sel_np))
                     for c in range(sp.n_chunks)]
-        for lw, (kp, vp) in zip(weights, pools):
+        for lw, (kp, vp) in zip(weights, use_pools):
             if compact:
                 parts = []
                 for c in range(sp.n_chunks):
@@ -215,7 +221,7 @@ def bench_stack(args, B, W, np, torch) -> int:
                 continue
             ch = B.make_chunks([dict(k=kp[c * sp.chunk_len:(c + 1) * sp.chunk_len], v=vp[c * sp.chunk_len:(c + 1) * sp.chunk_len],
                                      n_tokens=sp.chunk_len, old_pos_start=0, new_pos_start=c * sp.chunk_len,
-                                     location=0 if args.kv_pool == "device" else 1)
+                                     location=0 if kv_pool == "device" else 1)
                                 for c in range(sp.n_chunks)])
             keep.append(ch)
             d = dict(lw)
@@ -233,7 +239,7 @@ def bench_stack(args, B, W, np, torch) -> int:
         def step():
             h.copy_(h0)
             torch.cuda.current_stream().synchronize()
-            B.ct_partial_prefill_stack(cfg, ffn, 1e-5, layers, n_layers, sp.n_chunks, h, sel, n_sel, ratio_pct / 100.0,
+            B.ct_partial_prefill_stack(cfg, ffn, 1e-5, layers, n_layers, sp.n_chunks, h, sel, n_sel, min(r, 1.0),
                                        k_bufs, v_bufs, ws, ws_bytes, s1, s2)
         for _ in range(warmup):
             step()
@@ -255,10 +261,47 @@ def bench_stack(args, B, W, np, torch) -> int:
         assert torch.isfinite(h.float()).all()
         return ms, n_sel, kern
 
-    log(f"partial prefill r={sp.ratio_pct}%")
-    ms_part, n_sel, kern_part = run(sp.ratio_pct, args.steps, args.warmup)
+    tuning = None
+    ratio = sp.ratio_pct / 100.0
+    if args.tune_ratio:
+        # Sec. 4.3 on this machine.  Hardware profile: t_c and t_o from the compute-only stack
+        # (device-resident pool) at two ratios, t_i from the transfer-dominated stack (this pool, 2 %);
+        # then Alg. 1 over the measured latency of the stack, warm-started at the prior of Eq. 11.
+        r_a, r_b, r_s = 0.15, 0.30, 0.02
+        la = run(r_a, args.steps, 1, "device")[0] / n_layers
+        lb = run(r_b, args.steps, 1, "device")[0] / n_layers
+        t_c = (lb - la) / ((r_b - r_a) * N)
+        t_o = la - r_a * N * t_c
+        if args.kv_pool == "device":
+            t_i = 0.0
+        else:
+            ls = run(r_s, args.steps, 1)[0] / n_layers
+            t_i = max(0.0, (ls - t_o) / ((1.0 - r_s) * N))
+        r0_raw = t_i / (t_c + t_i)
+        r0 = B.ct_ratio_prior(t_c, t_i, args.r_min, args.r_max)
+        log(f"profile: t_c {t_c * 1e6:.1f} ns/token/layer, t_i {t_i * 1e6:.1f} ns/token/layer, t_o {t_o * 1e3:.1f} us/layer; "
+            f"crossover {r0_raw:.4f}, prior r0 {r0:.4f}")
+        probes = []
+
+        def ttft(r):
+            ms = run(r, args.steps, 1)[0]
+            probes.append({"r": r, "ms": ms, "model_ms": n_layers * B.ct_layer_latency_model(r, N, t_c, t_i, t_o)})
+            log(f"  probe r={r:.4f}: {ms:.2f} ms (model {probes[-1]['model_ms']:.2f})")
+            return ms
+        r_star, n_evals = B.ct_ratio_search(ttft, r0, args.r_min, args.r_max, args.eps, 32)
+        log(f"r* = {r_star:.4f} after {n_evals} evaluations")
+        tuning = {"t_c_ns_per_token_layer": t_c * 1e6, "t_i_ns_per_token_layer": t_i * 1e6, "t_o_us_per_layer": t_o * 1e3,
+                  "profile_points": {"device_pool_ms_per_layer": {str(r_a): la, str(r_b): lb},
+                                     "this_pool_ms_per_layer": None if args.kv_pool == "device" else {str(r_s): ls}},
+                  "crossover_unclipped": r0_raw, "r0": r0, "r_min": args.r_min, "r_max": args.r_max, "eps": args.eps,
+                  "n_evals": n_evals, "r_star": r_star, "probes": probes,
+                  "calibration_set": f"{args.steps} seeded synthetic steps per probe"}
+        ratio = r_star
+    rtxt = f"{ratio * 100:.1f}%" if args.tune_ratio else f"{sp.ratio_pct}%"
+    log(f"partial prefill r={rtxt}")
+    ms_part, n_sel, kern_part = run(ratio, args.steps, args.warmup)
     log("full prefill (r=100%)")
-    ms_full, _, kern_full = run(100, max(1, args.steps // 4), 1)
+    ms_full, _, kern_full = run(1.0, max(1, args.steps // 4), 1)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -272,8 +315,7 @@ def bench_stack(args, B, W, np, torch) -> int:
             return W.bf16_bits_to_f64(t.cpu().view(torch.int16).numpy().view(np.uint16))
         lw = {k: f64(v) for k, v in weights[0].items()}
         kc, vc = f64(pools[0][0]), f64(pools[0][1])
-        spr = W.spec(5, sp.ratio_pct)
-        sel_np = W.select_indices(spr)
+        sel_np = W.select_indices(sp, n_sel)
         h0 = np.random.default_rng(1005).standard_normal((n_sel, E))
         rows = W.sample_rows(n_sel, args.cpu_sample_rows, seed=1005)
         old_pos = (np.arange(N) % sp.chunk_len).astype(np.int32)         # keys cached at chunk-local positions
@@ -301,7 +343,8 @@ def bench_stack(args, B, W, np, torch) -> int:
                          f"visible keys x{vis_all / vis_s:.1f}); output projection and FFN on the same rows "
                          f"({t_tail:.2f}s, scaled x{n_sel / len(rows):.1f}); times {n_layers} layers (extrapolated)"}
     line = {
-        "metric": f"end-to-end partial prefill latency, {n_layers}-layer stack @{N // 1024}K ctx, r={sp.ratio_pct}% (vs full prefill)",
+        "metric": f"end-to-end partial prefill latency, {n_layers}-layer stack @{N // 1024}K ctx, r={rtxt}"
+                  f"{' (tuned)' if args.tune_ratio else ''} (vs full prefill)",
         "value": ms_part, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_part, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -312,7 +355,7 @@ def bench_stack(args, B, W, np, torch) -> int:
         "extra": {"full_prefill_ms": ms_full, "speedup_vs_full_prefill": ms_full / ms_part,
                   "ms_per_layer_partial": ms_part / n_layers, "ms_per_layer_full": ms_full / n_layers,
                   "host_to_device_bytes_per_layer": 0 if args.kv_pool == "device" else 2 * (N - n_sel) * Hkv * D * 2,
-                  "kernels_partial": kern_part, "kernels_full": kern_full},
+                  "kernels_partial": kern_part, "kernels_full": kern_full, "ratio_tuning": tuning},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
@@ -330,6 +373,11 @@ def main() -> int:
                     help="config 5 only: where the per-layer cached K/V live (pinned host memory is the paper's CPU pool; "
                          "compact = pinned, holding only the rows that are not recomputed)")
     ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
+    ap.add_argument("--tune-ratio", action="store_true",
+                    help="config 5 only: profile t_c, t_i, t_o and search the ratio with the least measured latency")
+    ap.add_argument("--r-min", type=float, default=0.15)
+    ap.add_argument("--r-max", type=float, default=0.60)
+    ap.add_argument("--eps", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=96)
     ap.add_argument("--calibration-copy", action="store_true",

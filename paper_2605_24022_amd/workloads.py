@@ -174,9 +174,12 @@ def _select_clustered(rng, n_chunks, chunk_len, n_sel, edge=64, share=0.7):
     return np.sort(np.concatenate([clustered, extra]))
 
 
-def select_indices(sp: WorkloadSpec) -> np.ndarray:
+def select_indices(sp: WorkloadSpec, n_sel: Optional[int] = None) -> np.ndarray:
+    """The selected token indices, ascending.  `n_sel` overrides the count that follows from the
+    spec's percentage (for ratios that are not whole percents)."""
     rng = np.random.default_rng([sp.seed, 4])
-    n_ctx, n_sel = sp.n_ctx, sp.n_sel
+    n_ctx = sp.n_ctx
+    n_sel = sp.n_sel if n_sel is None else int(n_sel)
     if n_sel == 0:
         idx = np.empty(0, dtype=np.int64)
     elif sp.selection == "all" or n_sel == n_ctx:
