@@ -34,6 +34,12 @@ intermediate rounding:
                       golden-section search of Alg. 1.  The search is an iteration, so it is
                       written step by step in the algorithm's notation.
 
+  frequency_scores, topk_indices, select_frequency
+                      the offline frequency-domain choice of the tokens to recompute (Sec. 4.1):
+                      rFFT along the sequence (Eq. 2), low-pass (Eq. 3), inverse rFFT (Eq. 4),
+                      per-token norms (Eq. 5), joint score (Eq. 6), TopK (Eq. 7).  NumPy's FFT
+                      is the library step; everything else is the equations as written.
+
 Readings where the paper is silent (RoPE pair convention and frequencies, softmax scale,
 GQA head mapping, floor for r*N, V being position independent) are stated at the function
 that uses them.  All pins live in tests/test_oracle_pins.py.
@@ -305,3 +311,52 @@ def ratio_search(f, r0, r_min, r_max, eps, max_evals=64):
             x1, x2, f1 = s, s + (1.0 - phi) * (b - s), fs
             f2 = evaluate(x2)
     return (a + b) / 2.0, probes
+
+
+# ----------------------------------------------------------------------------- frequency-guided selection (Sec. 4.1)
+def lowpass_cutoff(n_tokens: int, alpha: float) -> int:
+    """Eq. 3: c = floor(alpha * (floor(N/2) + 1)); bins k >= c are zeroed.  (A 1e-9 guard keeps a
+    product that is an integer in exact arithmetic from falling below it in floating point.)"""
+    return int(np.floor(alpha * (n_tokens // 2 + 1) + 1e-9))
+
+
+def lowpass_reconstruction(x, alpha: float):
+    """Eq. 2-4 for one tensor x [N, ...]: transform along axis 0, zero the bins from the cutoff
+    on, transform back to N samples."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[0]
+    spec = np.fft.rfft(x, axis=0)
+    spec[lowpass_cutoff(n, alpha):] = 0.0
+    return np.fft.irfft(spec, n=n, axis=0)
+
+
+def frequency_scores(k, v, alpha: float):
+    """Eq. 5-6: s_i = (||K~_i||_2 + ||V~_i||_2) / 2, the norms taken over all heads and
+    dimensions of token i.  k, v: [N, H, D] (or [N, H*D]).  Returns float64 [N]."""
+    kt = lowpass_reconstruction(k, alpha)
+    vt = lowpass_reconstruction(v, alpha)
+    n = kt.shape[0]
+    s_k = np.sqrt((kt.reshape(n, -1) ** 2).sum(axis=1))
+    s_v = np.sqrt((vt.reshape(n, -1) ** 2).sum(axis=1))
+    return 0.5 * (s_k + s_v)
+
+
+def topk_indices(scores, k: int):
+    """Eq. 7: the k tokens with the largest scores, returned in ascending index order (the form
+    the online path takes its index set in).  Reading: among equal scores the lower index wins,
+    which makes the set unique."""
+    scores = np.asarray(scores)
+    n = scores.shape[0]
+    order = sorted(range(n), key=lambda i: (-float(scores[i]), i))
+    return np.array(sorted(order[:k]), dtype=np.int32)
+
+
+def select_frequency(k, v, alpha: float, ratio: float):
+    """The recomputation set of one chunk and layer: TopK of the scores with floor(r N) entries
+    (at least one when r > 0).  Returns (indices, scores)."""
+    s = frequency_scores(k, v, alpha)
+    n = s.shape[0]
+    n_sel = n if ratio >= 1.0 else int(np.floor(ratio * n + 1e-9))
+    if ratio > 0.0 and n_sel < 1:
+        n_sel = 1
+    return topk_indices(s, n_sel), s

@@ -301,3 +301,28 @@ def make_stack_workload(sp: WorkloadSpec, n_layers: int, ffn_dim: int, rms_eps: 
                          (i % sp.chunk_len).astype(np.int32), i.copy(), sel,
                          np.concatenate([c * sp.chunk_len, [n_ctx]]).astype(np.int32),
                          (c * sp.chunk_len).astype(np.int32))
+
+
+# --------------------------------------------------------------------------- chunk K/V for the offline scoring
+def make_spectral_kv(seed: int, n_tokens: int, row_elems: int, n_batch: int = 1):
+    """Synthetic per-chunk K and V with structure along the sequence, standing in for the cached
+    K/V of real chunks: per column a few slow sinusoids (random frequency below N/16, amplitude,
+    phase) and a slow drift, white noise of comparable size on top, a per-token gain that makes
+    about 3 % of the tokens stand out by 2-4x (attention-sink-like rows), so that low-pass
+    scores separate tokens.  Returns two uint16 (bf16 bits) arrays [n_batch, n_tokens, row_elems]."""
+    out = []
+    for t in range(2):
+        rng = np.random.default_rng([seed, 70 + t])
+        n = np.arange(n_tokens, dtype=np.float64)[None, :, None]
+        x = rng.standard_normal((n_batch, n_tokens, row_elems))
+        for _ in range(3):
+            f = rng.uniform(0.0, max(1.0, n_tokens / 16.0), (n_batch, 1, row_elems))
+            a = rng.uniform(0.2, 1.0, (n_batch, 1, row_elems))
+            ph = rng.uniform(0.0, 2 * np.pi, (n_batch, 1, row_elems))
+            x += a * np.cos(2 * np.pi * f * n / n_tokens + ph)
+        x += rng.standard_normal((n_batch, 1, row_elems)) * (n / max(1, n_tokens) - 0.5)
+        gain = np.ones((n_batch, n_tokens, 1))
+        hot = rng.random((n_batch, n_tokens, 1)) < 0.03
+        gain[hot] = rng.uniform(2.0, 4.0, int(hot.sum()))
+        out.append(f32_to_bf16_bits((x * gain).astype(np.float32)))
+    return out[0], out[1]

@@ -497,3 +497,88 @@ def test_ratio_search_degenerate_brackets():
     assert r_star == pytest.approx(0.2002) and probes == [] and calls == []
     r_star, probes = O.ratio_search(f, 0.5, 0.1, 0.9, 1e-6, max_evals=5)
     assert len(probes) == 5 and 0.1 < r_star < 0.9
+
+
+# ----------------------------------------------------------------------------- frequency-guided selection (Sec. 4.1)
+def _lowpass_by_definition(x, c):
+    """x~_i = (1/N) sum_j x_j [1 + 2 sum_{0<k<c, k<N/2} cos(2 pi k (i-j)/N) + (-1)^(i-j) if the
+    Nyquist bin of an even N is kept]: the real DFT pair written as a sum, no FFT."""
+    n = x.shape[0]
+    out = np.zeros_like(x, dtype=np.float64)
+    for i in range(n):
+        for j in range(n):
+            w = 1.0 if c > 0 else 0.0
+            for k in range(1, c):
+                if 2 * k < n:
+                    w += 2.0 * math.cos(2 * math.pi * k * (i - j) / n)
+                elif 2 * k == n:
+                    w += (-1.0) ** (i - j)
+            out[i] += w * x[j] / n
+    return out
+
+
+@pytest.mark.parametrize("n,alpha", [(8, 0.5), (9, 0.5), (12, 0.3), (15, 0.7), (16, 1.0), (7, 1.0), (10, 0.05), (2, 0.5), (1, 0.5)])
+def test_lowpass_reconstruction_against_the_dft_written_out(n, alpha):
+    rng = np.random.default_rng([61, n])
+    x = rng.standard_normal((n, 3))
+    c = int(math.floor(alpha * (n // 2 + 1) + 1e-9))
+    assert O.lowpass_cutoff(n, alpha) == c
+    np.testing.assert_allclose(O.lowpass_reconstruction(x, alpha), _lowpass_by_definition(x, c), atol=1e-12)
+
+
+def test_cutoff_arithmetic():
+    # N = 2048: 1025 bins, alpha = 0.5 -> 512; N = 3072: 1537 bins -> 768; alpha = 1 keeps all bins
+    assert O.lowpass_cutoff(2048, 0.5) == 512
+    assert O.lowpass_cutoff(3072, 0.5) == 768
+    assert O.lowpass_cutoff(4096, 0.3) == 614          # floor(0.3 * 2049) = floor(614.7)
+    assert O.lowpass_cutoff(2048, 1.0) == 1025
+    assert O.lowpass_cutoff(10, 0.5) == 3 and O.lowpass_cutoff(1, 0.5) == 0
+
+
+def test_scores_closed_forms():
+    """alpha = 1 keeps the signal, so the score is the plain row norm; a constant column passes any
+    filter with c >= 1; a sinusoid passes when its bin is below the cutoff and vanishes when not;
+    a circular shift of the tokens shifts the scores; the kept energy obeys Parseval."""
+    rng = np.random.default_rng(62)
+    n, h, d = 48, 2, 4
+    k, v = rng.standard_normal((n, h, d)), rng.standard_normal((n, h, d))
+    want = 0.5 * (np.linalg.norm(k.reshape(n, -1), axis=1) + np.linalg.norm(v.reshape(n, -1), axis=1))
+    np.testing.assert_allclose(O.frequency_scores(k, v, 1.0), want, rtol=1e-12)
+    const = np.ones((n, h, d)) * 3.0
+    np.testing.assert_allclose(O.frequency_scores(const, 2 * const, 0.1), np.full(n, 0.5 * (3 + 6) * math.sqrt(h * d)), rtol=1e-12)
+    t = np.arange(n)
+    c = O.lowpass_cutoff(n, 0.5)      # 25 bins -> c = 12
+    assert c == 12
+    low = np.cos(2 * np.pi * 5 * t / n)[:, None, None] * np.ones((1, h, d))
+    high = np.cos(2 * np.pi * 12 * t / n + 0.3)[:, None, None] * np.ones((1, h, d))
+    s = O.frequency_scores(low + high, np.zeros((n, h, d)), 0.5)
+    np.testing.assert_allclose(s, 0.5 * np.abs(np.cos(2 * np.pi * 5 * t / n)) * math.sqrt(h * d), atol=1e-12)
+    np.testing.assert_allclose(O.frequency_scores(np.roll(k, 7, axis=0), np.roll(v, 7, axis=0), 0.4),
+                               np.roll(O.frequency_scores(k, v, 0.4), 7), rtol=1e-12)
+    kt = O.lowpass_reconstruction(k, 0.4)
+    spec = np.fft.fft(k, axis=0)
+    cc = O.lowpass_cutoff(n, 0.4)
+    kept = [f for f in range(n) if min(f, n - f) < cc]
+    assert (kt ** 2).sum() == pytest.approx((np.abs(spec[kept]) ** 2).sum() / n, rel=1e-12)
+    # the two halves of Eq. 6 are not interchangeable with a joint norm: K and V enter separately
+    s_kv = O.frequency_scores(k, np.zeros_like(v), 0.4) + O.frequency_scores(np.zeros_like(k), v, 0.4)
+    np.testing.assert_allclose(O.frequency_scores(k, v, 0.4), s_kv, rtol=1e-12)
+
+
+def test_topk_against_rank_counting_with_ties():
+    rng = np.random.default_rng(63)
+    for n in (1, 2, 17, 200):
+        s = rng.integers(0, 6, n).astype(np.float64)          # many ties
+        for k in sorted({0, 1, n // 3, n - 1, n} & set(range(n + 1))):
+            rank = [(sum(1 for j in range(n) if s[j] > s[i] or (s[j] == s[i] and j < i))) for i in range(n)]
+            want = [i for i in range(n) if rank[i] < k]
+            got = O.topk_indices(s, k)
+            assert got.dtype == np.int32 and got.tolist() == want
+    s = rng.standard_normal(1000)
+    got = O.topk_indices(s, 150)
+    assert sorted(got.tolist()) == sorted(np.argsort(-s)[:150].tolist())
+    idx, sc = O.select_frequency(rng.standard_normal((40, 2, 4)), rng.standard_normal((40, 2, 4)), 0.5, 0.15)
+    assert idx.size == 6 and np.all(np.diff(idx) > 0) and sc[idx].min() >= np.delete(sc, idx).max()
+    assert O.select_frequency(np.ones((40, 1, 2)), np.ones((40, 1, 2)), 0.5, 0.01)[0].size == 1
+    assert O.select_frequency(np.ones((40, 1, 2)), np.ones((40, 1, 2)), 0.5, 0.0)[0].size == 0
+    assert O.select_frequency(np.ones((40, 1, 2)), np.ones((40, 1, 2)), 0.5, 1.0)[0].tolist() == list(range(40))
