@@ -253,6 +253,40 @@ typedef double (*ct_ttft_fn)(double r, void* user);
 ct_status ct_ratio_search(ct_ttft_fn eval, void* user, double r0, double r_min, double r_max, double eps,
                           int32_t max_evals, double* r_star, int32_t* n_evals);
 
+/* ---- Offline choice of the tokens to recompute (Sec. 4.1): done once per chunk and layer when
+ * the chunk's cache is generated; its result is the index set the calls above consume. ---- */
+
+/* Low-frequency energy scores, Eq. 2-6.  For each of n_batch sequences (say, the layers of one
+ * chunk): real FFT of every (head, dim) column of K and of V along the tokens, bins
+ * k >= c = floor(alpha * (floor(N/2) + 1)) zeroed, inverse real FFT back to N samples, then
+ * scores[b, i] = (||K~_i||_2 + ||V~_i||_2) / 2 with the norms over the row_elems = H * D values
+ * of token i.  fp32 arithmetic on bf16 inputs; the result does not depend on launch order.
+ *   k, v        device bf16 [n_batch][n_tokens, row_elems], sequence b at element offset
+ *               b * batch_stride (batch_stride >= n_tokens * row_elems)
+ *   scores      device fp32 [n_batch, n_tokens]
+ *   workspace   at least ct_frequency_workspace_bytes() bytes of device memory
+ * n_tokens must be of the form 2^a 3^b 5^c and at most 4096 (the transform of a strip of columns
+ * is done inside one compute unit's LDS); row_elems even.  CT_ERR_UNSUPPORTED otherwise. */
+ct_status ct_frequency_scores(const void* k, const void* v, int32_t n_batch, int64_t batch_stride, int32_t n_tokens,
+                              int32_t row_elems, double alpha, float* scores, void* workspace, size_t workspace_bytes,
+                              void* stream);
+size_t ct_frequency_workspace_bytes(int32_t n_batch, int32_t n_tokens, int32_t row_elems);
+
+/* TopK, Eq. 7: for each of n_batch score rows the k positions with the largest scores, written
+ * in ascending position order (int32 [n_batch, k]).  Equal scores: the lower position wins, so
+ * the set is unique.  Scores must not be NaN.  k = 0 writes nothing. */
+ct_status ct_topk_indices(const float* scores, int32_t n_batch, int32_t n_tokens, int32_t k, int32_t* idx_out,
+                          void* stream);
+
+/* floor(ratio * n_tokens), at least 1 when ratio > 0: the size of the recomputation set. */
+int32_t ct_frequency_n_selected(int32_t n_tokens, double ratio);
+
+/* Eq. 2-7 in one call: scores (also returned, [n_batch, n_tokens]) and the recomputation sets
+ * idx_out [n_batch, ct_frequency_n_selected(n_tokens, ratio)], each ascending. */
+ct_status ct_select_frequency(const void* k, const void* v, int32_t n_batch, int64_t batch_stride, int32_t n_tokens,
+                              int32_t row_elems, double alpha, double ratio, int32_t* idx_out, float* scores,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host-side check of an index set: strictly ascending and inside [0, n_ctx). */
 ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_ctx);
 
@@ -262,7 +296,7 @@ ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_
  * times and returns the number of launches and the summed milliseconds; ct_profile_reset
  * forgets what was recorded.  Classes: 0 qkv projection, 1 re-RoPE, 2 scatter,
  * 3 selected attention (main kernel), 4 attention split merge, 5 linear / SwiGLU GEMMs,
- * 6 RMSNorm.  Profiling is process wide,
+ * 6 RMSNorm, 7 frequency scores, 8 TopK.  Profiling is process wide,
  * off by default, creates events on first use and is not meant for concurrent callers. */
 void ct_set_profiling(int32_t on);
 void ct_profile_reset(void);

@@ -18,7 +18,7 @@ CT_OK = 0
 CT_ERR_NULL, CT_ERR_SHAPE, CT_ERR_INDEX, CT_ERR_RATIO = -1, -2, -3, -4
 CT_ERR_WORKSPACE, CT_ERR_HIP, CT_ERR_UNSUPPORTED = -5, -6, -7
 
-KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 4, "linear": 5, "norm": 6}
+KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 4, "linear": 5, "norm": 6, "frequency": 7, "topk": 8}
 
 EXPORTS = [
     "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
@@ -26,6 +26,8 @@ EXPORTS = [
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
     "ct_rmsnorm", "ct_linear", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
     "ct_measure_mfma_rate", "ct_layer_latency_model", "ct_ratio_prior", "ct_ratio_search",
+    "ct_frequency_scores", "ct_frequency_workspace_bytes", "ct_topk_indices", "ct_frequency_n_selected",
+    "ct_select_frequency",
 ]
 
 
@@ -91,6 +93,15 @@ def load() -> ctypes.CDLL:
     lib.ct_profile_reset.argtypes = []
     lib.ct_profile_reset.restype = None
     lib.ct_profile_read.argtypes = [c_int32, POINTER(c_int64), POINTER(c_double)]
+    lib.ct_frequency_scores.argtypes = [c_void_p, c_void_p, c_int32, c_int64, c_int32, c_int32, c_double, c_void_p,
+                                        c_void_p, c_size_t, c_void_p]
+    lib.ct_frequency_workspace_bytes.argtypes = [c_int32, c_int32, c_int32]
+    lib.ct_frequency_workspace_bytes.restype = c_size_t
+    lib.ct_topk_indices.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+    lib.ct_frequency_n_selected.argtypes = [c_int32, c_double]
+    lib.ct_frequency_n_selected.restype = c_int32
+    lib.ct_select_frequency.argtypes = [c_void_p, c_void_p, c_int32, c_int64, c_int32, c_int32, c_double, c_double,
+                                        c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.ct_layer_latency_model.argtypes = [c_double] * 5
     lib.ct_layer_latency_model.restype = c_double
     lib.ct_ratio_prior.argtypes = [c_double] * 4
@@ -252,6 +263,30 @@ def ct_set_profiling(on: bool) -> None:
 
 def ct_profile_reset() -> None:
     load().ct_profile_reset()
+
+
+def ct_frequency_workspace_bytes(n_batch, n_tokens, row_elems) -> int:
+    return int(load().ct_frequency_workspace_bytes(n_batch, n_tokens, row_elems))
+
+
+def ct_frequency_scores(k, v, n_batch, batch_stride, n_tokens, row_elems, alpha, scores, workspace, workspace_bytes,
+                        stream=None):
+    _check(load().ct_frequency_scores(_ptr(k), _ptr(v), n_batch, batch_stride, n_tokens, row_elems, alpha, _ptr(scores),
+                                      _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def ct_topk_indices(scores, n_batch, n_tokens, k, idx_out, stream=None):
+    _check(load().ct_topk_indices(_ptr(scores), n_batch, n_tokens, k, _ptr(idx_out), _stream(stream)))
+
+
+def ct_frequency_n_selected(n_tokens, ratio) -> int:
+    return int(load().ct_frequency_n_selected(n_tokens, ratio))
+
+
+def ct_select_frequency(k, v, n_batch, batch_stride, n_tokens, row_elems, alpha, ratio, idx_out, scores, workspace,
+                        workspace_bytes, stream=None):
+    _check(load().ct_select_frequency(_ptr(k), _ptr(v), n_batch, batch_stride, n_tokens, row_elems, alpha, ratio,
+                                      _ptr(idx_out), _ptr(scores), _ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def ct_layer_latency_model(r, n_tokens, t_c, t_i, t_o) -> float:

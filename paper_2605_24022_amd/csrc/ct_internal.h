@@ -9,7 +9,7 @@
 namespace ct {
 
 // ---- kernel classes for the opt-in event profiling ------------------------------------
-enum KernelClass { KC_QKV = 0, KC_REROPE = 1, KC_SCATTER = 2, KC_ATTN = 3, KC_MERGE = 4, KC_LINEAR = 5, KC_NORM = 6, KC_COUNT = 7 };
+enum KernelClass { KC_QKV = 0, KC_REROPE = 1, KC_SCATTER = 2, KC_ATTN = 3, KC_MERGE = 4, KC_LINEAR = 5, KC_NORM = 6, KC_FREQ = 7, KC_TOPK = 8, KC_COUNT = 9 };
 
 ct_status fail(ct_status code, const char* fmt, ...);
 ct_status hip_fail(hipError_t e, const char* what);

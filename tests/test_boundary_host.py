@@ -219,3 +219,26 @@ def test_stack_validation():
     assert call(entries=bad) == B.CT_ERR_NULL
     # pinned-host chunks need a second stream (both default here)
     assert call(entries=_layers(location=1), ws=FAKE) == B.CT_ERR_SHAPE
+
+
+def test_frequency_selection_argument_checks():
+    """Everything the host can reject is rejected before any HIP call."""
+    lib = B.load()
+    one = ctypes.c_void_p(256)     # never dereferenced: the checks fail first
+    def scores(n_batch=1, stride=2048 * 1024, n=2048, row=1024, alpha=0.5, k=one, v=one, out=one, ws=one, ws_bytes=1 << 30):
+        return lib.ct_frequency_scores(k, v, n_batch, stride, n, row, alpha, out, ws, ws_bytes, None)
+    assert scores(n=7 * 128) == B.CT_ERR_UNSUPPORTED          # prime factor 7
+    assert scores(n=8192, stride=8192 * 1024) == B.CT_ERR_UNSUPPORTED
+    assert scores(row=1023) == B.CT_ERR_SHAPE
+    assert scores(alpha=1.5) == B.CT_ERR_RATIO and scores(alpha=-0.1) == B.CT_ERR_RATIO
+    assert scores(k=None) == B.CT_ERR_NULL and scores(out=None) == B.CT_ERR_NULL
+    assert scores(n_batch=2, stride=100) == B.CT_ERR_SHAPE
+    assert scores(ws_bytes=16) == B.CT_ERR_WORKSPACE and scores(ws=None) == B.CT_ERR_WORKSPACE
+    assert scores(n_batch=0) == B.CT_OK and scores(n=0) == B.CT_OK
+    assert B.ct_frequency_workspace_bytes(1, 2048, 1024) == 2 * 64 * 2048 * 4
+    assert B.ct_frequency_workspace_bytes(1, 8192, 1024) == 0 and B.ct_frequency_workspace_bytes(1, 7, 8) == 0
+    assert lib.ct_topk_indices(one, 1, 10, 11, one, None) == B.CT_ERR_SHAPE
+    assert lib.ct_topk_indices(None, 1, 10, 3, one, None) == B.CT_ERR_NULL
+    assert lib.ct_topk_indices(one, 1, 10, 0, one, None) == B.CT_OK
+    assert [B.ct_frequency_n_selected(32768, r) for r in (0.0, 0.15, 1e-9, 1.0)] == [0, 4915, 1, 32768]
+    assert lib.ct_select_frequency(one, one, 1, 0, 2048, 1024, 0.5, 1.2, one, one, one, 1 << 30, None) == B.CT_ERR_RATIO
