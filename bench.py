@@ -154,6 +154,89 @@ def cold_cache_bandwidth(B, cfg, wl, sp, torch, np, reps: int = 3):
     return res
 
 
+def bench_offline(args, B, W, np, torch) -> int:
+    """Offline frequency-guided selection (Sec. 4.1) for one chunk of the config-3/5 shape, all
+    layers in one call: K and V of `--layers` layers x 2048 tokens x 1024 values, alpha = 0.5,
+    r = `--ratio` %.  A step is one ct_select_frequency call (scores + TopK); buffers rotate
+    through a ring of more than 1 GiB so that no step finds its input in the last-level cache."""
+    n, row, n_batch, alpha = 2048, 1024, args.layers, 0.5
+    ratio = args.ratio / 100.0
+    n_sel = B.ct_frequency_n_selected(n, ratio)
+    log(f"generating spectral K/V for {n_batch} layers of a {n}-token chunk")
+    kb, vb = W.make_spectral_kv(1006, n, row, min(n_batch, 4))
+    reps = (n_batch + kb.shape[0] - 1) // kb.shape[0]
+
+    def dev(bits):
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+        return t.repeat(reps, 1, 1)[:n_batch].contiguous()
+    bytes_per_step = n_batch * (2 * n * row * 2 + n * 4 + n_sel * 4)
+    ring = max(2, -(-(1 << 30) // (n_batch * 2 * n * row * 2)) + 1)
+    ks = [dev(kb) for _ in range(ring)]
+    vs = [dev(vb) for _ in range(ring)]
+    ws_bytes = B.ct_frequency_workspace_bytes(n_batch, n, row)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    scores = torch.empty((n_batch, n), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n_batch, n_sel), dtype=torch.int32, device="cuda")
+
+    def step(i):
+        B.ct_select_frequency(ks[i % ring], vs[i % ring], n_batch, n * row, n, row, alpha, ratio, idx, scores, ws, ws_bytes)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    B.ct_profile_reset()
+    B.ct_set_profiling(not args.no_profile_events)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    B.ct_set_profiling(False)
+    cnt_f, ms_f = B.ct_profile_read("frequency")
+    cnt_t, ms_t = B.ct_profile_read("topk")
+    B.ct_profile_reset()
+    us_f = ms_f / max(cnt_f, 1) * 1e3
+    us_t = ms_t / max(cnt_t, 1) * 1e3
+    score_bytes = n_batch * (2 * n * row * 2 + n * 4)
+    fft_flop = n_batch * 2 * (row // 2) * 2 * 5.0 * n * math.log2(n)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        from oracle import ct_oracle as O
+        nb = min(4, n_batch)
+        log(f"timing the CPU oracle on {nb} layers")
+        kf, vf = W.bf16_bits_to_f64(kb[:nb]), W.bf16_bits_to_f64(vb[:nb])
+        t0 = time.perf_counter()
+        want = [O.select_frequency(kf[b], vf[b], alpha, ratio) for b in range(nb)]
+        t_cpu = (time.perf_counter() - t0) / nb
+        step(0)
+        torch.cuda.synchronize()
+        agree = [int(np.isin(want[b][0], idx[b].cpu().numpy()).sum()) for b in range(nb)]
+        threads = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+        cpu = {"value": t_cpu * n_batch * 1e3, "unit": "ms", "cores": threads, "kind": "oracle",
+               "sample": f"fp64 NumPy oracle (rfft, mask, irfft, norms, sort) on {nb} of {n_batch} layers, scaled; "
+                         f"indices equal to the oracle's: {agree} of {n_sel} per layer"}
+    line = {
+        "metric": f"offline frequency-guided selection, {n_batch} layers of a {n}-token chunk, r={args.ratio}%",
+        "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"offline-select-llama8b-chunk{n}-x{n_batch}", "n_tokens": n, "row_elems": row,
+                   "alpha": alpha, "n_sel": n_sel},
+        # bound by vector arithmetic: a forward and an inverse complex FFT of length N (5 N log2 N flop
+        # each, the usual count) for each of the row_elems / 2 packed column pairs of K and of V
+        "roofline": {"bound": "alu", "achieved": fft_flop / (us_f * 1e-6) / 1e12 if us_f else None, "peak": 157.3,
+                     "unit": "TFLOP/s", "frac": fft_flop / (us_f * 1e-6) / 157.3e12 if us_f else None, "traffic": None,
+                     "kernel": "freq_energy_kernel (+ freq_finish_kernel), cold cache"},
+        "extra": {"scores_us": us_f, "topk_us": us_t, "algorithmic_bytes_per_step": bytes_per_step,
+                  "algorithmic_flop_per_step": fft_flop,
+                  "scores_hbm_GBps": score_bytes / (us_f * 1e-6) / 1e9 if us_f else None,
+                  "scores_frac_of_hbm_peak": score_bytes / (us_f * 1e-6) / 8e12 if us_f else None,
+                  "us_per_chunk_layer": ms * 1e3 / n_batch},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
 def bench_stack(args, B, W, np, torch) -> int:
     """Config 5: Llama-3-8B-shaped stack (hidden 4096, FFN 14336, 32/8 heads) over a 32768-token
     context; partial prefill at the given ratio with per-layer KV streamed from pinned host
@@ -373,6 +456,8 @@ def main() -> int:
                     help="config 5 only: where the per-layer cached K/V live (pinned host memory is the paper's CPU pool; "
                          "compact = pinned, holding only the rows that are not recomputed)")
     ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
+    ap.add_argument("--offline-select", action="store_true",
+                    help="time the offline frequency-guided selection (scores + TopK) instead of the online path")
     ap.add_argument("--tune-ratio", action="store_true",
                     help="config 5 only: profile t_c, t_i, t_o and search the ratio with the least measured latency")
     ap.add_argument("--r-min", type=float, default=0.15)
@@ -406,6 +491,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     B.load()
 
+    if args.offline_select:
+        return bench_offline(args, B, W, np, torch)
     if args.config == 5:
         return bench_stack(args, B, W, np, torch)
 

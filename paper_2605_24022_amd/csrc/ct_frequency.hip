@@ -20,8 +20,10 @@
 
 namespace ct {
 
+// One workgroup of 1024 threads per compute unit.  (Two of 512 threads with half the strip each
+// were measured: no faster, the kernel is bound by vector instructions, not by waiting.)
 constexpr int kFreqThreads = 1024;
-constexpr int kFreqMaxElems = 16384;   // complex values of a strip held in LDS (and 16 per thread)
+constexpr int kFreqMaxElems = 16384;   // complex values of a strip held in LDS (16 per thread)
 constexpr int kFreqMaxTokens = 4096;
 
 struct FftPlan {
@@ -31,7 +33,7 @@ struct FftPlan {
   int32_t radix[12];
   int32_t cutoff;     // bins k with min(k, n - k) >= cutoff are zeroed
   int32_t strips;     // strips per tensor = row_elems / (2 CP)
-  int32_t groups;     // workgroups per tensor; workgroup g owns strips g, g + groups, ...
+  int32_t groups;     // workgroups per tensor; workgroup g owns strips g * (strips / groups) ... in order
 };
 
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
@@ -129,28 +131,44 @@ __device__ __forceinline__ int phys(int n, int c, int lg_cp) { return ((n + (n >
 
 // One Stockham pass of radix R over all CP sequences.  ns = product of the radices of the
 // passes before this one.  tw[t] = exp(-2 pi i t / n) for t < n / 2.
-template <int R>
-__device__ __forceinline__ void stockham_pass(float2* data, const float2* tw, int n, int lg_cp, int ns, float sgn) {
+// N_CT > 0: the length (a power of two, with CP = kFreqMaxElems / N sequences per strip) and ns are known
+// at compile time, which turns the index arithmetic into shifts and immediate offsets; N_CT = 0
+// takes them at run time.
+template <int R, int N_CT, int NS_CT>
+__device__ __forceinline__ void stockham_pass(float2* data, const float2* tw, int n_rt, int lg_cp_rt, int ns_rt,
+                                              float sgn) {
+  constexpr bool FIXED = N_CT > 0;
   constexpr int ITER = (kFreqMaxElems / kFreqThreads + R - 1) / R;
+  const int n = FIXED ? N_CT : n_rt;
+  const int lg_cp = FIXED ? __builtin_ctz(kFreqMaxElems / (FIXED ? N_CT : 1)) : lg_cp_rt;
+  const int ns = FIXED ? NS_CT : ns_rt;
   const int m = n / R;                 // butterflies per sequence
   const int nb = m << lg_cp;
   const int cmask = (1 << lg_cp) - 1;
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));        // addresses are computed here, not hoisted out of the strip loop
   float2 v[ITER][R];
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
-    const int b = threadIdx.x + i * kFreqThreads;
-    if (b < nb) {
+    const int b = tid + i * kFreqThreads;
+    if (FIXED || b < nb) {
       const int j = b >> lg_cp, c = b & cmask;
+      if (FIXED && (N_CT / R) % 16 == 0) {      // the stride is whole groups of 16 rows: constant offsets
+        const float2* src = data + phys(j, c, lg_cp);
 #pragma unroll
-      for (int r = 0; r < R; ++r) v[i][r] = data[phys(j + r * m, c, lg_cp)];
+        for (int r = 0; r < R; ++r) v[i][r] = src[(r * (m + m / 16)) << lg_cp];
+      } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[i][r] = data[phys(j + r * m, c, lg_cp)];
+      }
     }
   }
   __syncthreads();
   const int tstep = n / (ns * R);
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
-    const int b = threadIdx.x + i * kFreqThreads;
-    if (b < nb) {
+    const int b = tid + i * kFreqThreads;
+    if (FIXED || b < nb) {
       const int j = b >> lg_cp, c = b & cmask;
       const int hi = j / ns, k = j - hi * ns;
       if (ns > 1) {
@@ -172,13 +190,22 @@ __device__ __forceinline__ void stockham_pass(float2* data, const float2* tw, in
       }
       dft<R>(v[i], sgn);
       const int j0 = hi * ns * R + k;
+      if (FIXED && (NS_CT % 16 == 0 || (NS_CT == 1 && 16 % R == 0))) {
+        // rows j0 + r ns: whole groups of 16 rows apart, or (ns = 1) inside one group
+        float2* dst = data + phys(j0, c, lg_cp);
+        const int stride = NS_CT == 1 ? 1 : ns + ns / 16;
 #pragma unroll
-      for (int r = 0; r < R; ++r) data[phys(j0 + r * ns, c, lg_cp)] = v[i][r];
+        for (int r = 0; r < R; ++r) dst[(r * stride) << lg_cp] = v[i][r];
+      } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) data[phys(j0 + r * ns, c, lg_cp)] = v[i][r];
+      }
     }
   }
   __syncthreads();
 }
 
+// Run-time plan: any length of the form 2^a 3^b 5^c.
 __device__ __forceinline__ void transform(float2* data, const float2* tw, const FftPlan& p, int n, int lg_cp,
                                           float sgn) {
   int ns = 1;
@@ -186,32 +213,45 @@ __device__ __forceinline__ void transform(float2* data, const float2* tw, const 
     const int r = p.radix[s];
     asm volatile("" : "+s"(n), "+s"(lg_cp));
     switch (r) {
-      case 16: stockham_pass<16>(data, tw, n, lg_cp, ns, sgn); break;
-      case 8: stockham_pass<8>(data, tw, n, lg_cp, ns, sgn); break;
-      case 5: stockham_pass<5>(data, tw, n, lg_cp, ns, sgn); break;
-      case 4: stockham_pass<4>(data, tw, n, lg_cp, ns, sgn); break;
-      case 3: stockham_pass<3>(data, tw, n, lg_cp, ns, sgn); break;
-      default: stockham_pass<2>(data, tw, n, lg_cp, ns, sgn); break;
+      case 16: stockham_pass<16, 0, 0>(data, tw, n, lg_cp, ns, sgn); break;
+      case 8: stockham_pass<8, 0, 0>(data, tw, n, lg_cp, ns, sgn); break;
+      case 5: stockham_pass<5, 0, 0>(data, tw, n, lg_cp, ns, sgn); break;
+      case 4: stockham_pass<4, 0, 0>(data, tw, n, lg_cp, ns, sgn); break;
+      case 3: stockham_pass<3, 0, 0>(data, tw, n, lg_cp, ns, sgn); break;
+      default: stockham_pass<2, 0, 0>(data, tw, n, lg_cp, ns, sgn); break;
     }
     ns *= r;
   }
 }
 
+// Compile-time plans for the power-of-two lengths 256 ... 4096 (three passes at most).
+template <int N>
+__device__ __forceinline__ void transform_fixed(float2* data, const float2* tw, float sgn) {
+  constexpr int R0 = N == 512 ? 8 : 16;
+  constexpr int R1 = (N == 512 || N == 1024) ? 8 : 16;
+  constexpr int R2 = N / (R0 * R1);     // 1 (N = 256), 8 or 16
+  stockham_pass<R0, N, 1>(data, tw, 0, 0, 0, sgn);
+  stockham_pass<R1, N, R0>(data, tw, 0, 0, 0, sgn);
+  if constexpr (R2 > 1) stockham_pass<R2, N, R0 * R1>(data, tw, 0, 0, 0, sgn);
+}
+
 // partial[((b * 2 + kv) * groups + g) * n + token] = sum over the workgroup's strips of
 // |N x~|^2 (the 1/N of the inverse transform is applied by the finishing kernel).
+template <int N_CT>
 __global__ __launch_bounds__(kFreqThreads) void freq_energy_kernel(const uint16_t* __restrict__ k,
                                                                    const uint16_t* __restrict__ v,
                                                                    int64_t batch_stride, int32_t row_elems, int32_t n_work,
                                                                    FftPlan p, float* __restrict__ partial) {
   extern __shared__ float2 lds[];
-  int n = p.n, lg_cp = p.lg_cp;
+  int n = N_CT > 0 ? N_CT : p.n, lg_cp = N_CT > 0 ? __builtin_ctz(kFreqMaxElems / (N_CT > 0 ? N_CT : 1)) : p.lg_cp;
   const int cp = 1 << lg_cp;
   float2* data = lds;
   float2* tw = lds + ((n + (n >> 4) + 1) << lg_cp);
   // workgroups that share 128-byte lines of the rows (adjacent strips) are given ids that differ
   // by 8, which puts them on the same XCD (and its L2) in the same wave of launches
   int w = blockIdx.x;
-  const int per_line = cp >= 32 ? 1 : 32 / cp;
+  const int own = p.strips / p.groups;                       // strips per workgroup
+  const int per_line = cp * own >= 32 ? 1 : 32 / (cp * own);
   if (n_work % (8 * per_line) == 0 && p.groups % per_line == 0) {
     const int xcd = w & 7, slot = w >> 3;
     w = (slot / per_line) * (8 * per_line) + xcd * per_line + slot % per_line;
@@ -219,7 +259,9 @@ __global__ __launch_bounds__(kFreqThreads) void freq_energy_kernel(const uint16_
   const int tensor = w / p.groups, g = w - tensor * p.groups;   // tensor = batch * 2 + kv
   const uint16_t* src = ((tensor & 1) ? v : k) + (int64_t)(tensor >> 1) * batch_stride;
 
-  for (int t = threadIdx.x; t < (n + 1) / 2; t += kFreqThreads) {
+  // only radices 8 and 16 occur in the compiled-in plans, so their first-power twiddles stop at n / 8
+  const int tw_len = N_CT > 0 ? N_CT / 8 : (n + 1) / 2;
+  for (int t = threadIdx.x; t < tw_len; t += kFreqThreads) {
     float s, c;
     const float turns = (float)t / (float)n;           // in [0, 1/2)
     sincospif(-2.f * turns, &s, &c);
@@ -227,19 +269,23 @@ __global__ __launch_bounds__(kFreqThreads) void freq_energy_kernel(const uint16_
   }
   const int elems = n << lg_cp;
   constexpr int PER = kFreqMaxElems / kFreqThreads;
-  float acc[PER];
+  // energy of the rows this thread owns (rows tid, tid + kFreqThreads, ...), summed over the strips
+  constexpr int ROWS = kFreqMaxTokens / kFreqThreads;
+  float acc[ROWS];
 #pragma unroll
-  for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+  for (int i = 0; i < ROWS; ++i) acc[i] = 0.f;
 
-  for (int strip = g; strip < p.strips; strip += p.groups) {
+  for (int strip = g * own; strip < (g + 1) * own; ++strip) {
     // the sizes are made opaque once per strip, and once more before each stage, so that the
     // addresses of every stage are computed where they are used instead of being hoisted out of
     // the loop together (which overflows the 128 registers a 1024-thread workgroup leaves a lane)
-    asm volatile("" : "+s"(n), "+s"(lg_cp));
+    if (N_CT == 0) asm volatile("" : "+s"(n), "+s"(lg_cp));
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const uint32_t* base = reinterpret_cast<const uint32_t*>(src) + (int64_t)strip * cp;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int e = threadIdx.x + i * kFreqThreads;
+      const int e = tid + i * kFreqThreads;
       if (e < elems) {
         const int row = e >> lg_cp, c = e & (cp - 1);
         const uint32_t pair = __builtin_nontemporal_load(base + (int64_t)row * (row_elems / 2) + c);
@@ -247,9 +293,13 @@ __global__ __launch_bounds__(kFreqThreads) void freq_energy_kernel(const uint16_
       }
     }
     __syncthreads();
-    asm volatile("" : "+s"(n), "+s"(lg_cp));
-    transform(data, tw, p, n, lg_cp, -1.f);
-    asm volatile("" : "+s"(n), "+s"(lg_cp));
+    if constexpr (N_CT > 0) {
+      transform_fixed<N_CT>(data, tw, -1.f);
+    } else {
+      asm volatile("" : "+s"(n), "+s"(lg_cp));
+      transform(data, tw, p, n, lg_cp, -1.f);
+      asm volatile("" : "+s"(n), "+s"(lg_cp));
+    }
     // Eq. 3: bins from the cutoff on (and their mirror images) are zeroed
     {
       const int first = p.cutoff, last = p.cutoff == 0 ? n - 1 : n - p.cutoff;   // bins first..last go
@@ -260,27 +310,36 @@ __global__ __launch_bounds__(kFreqThreads) void freq_energy_kernel(const uint16_
       }
     }
     __syncthreads();
-    asm volatile("" : "+s"(n), "+s"(lg_cp));
-    transform(data, tw, p, n, lg_cp, 1.f);
-    asm volatile("" : "+s"(n), "+s"(lg_cp));
+    if constexpr (N_CT > 0) {
+      transform_fixed<N_CT>(data, tw, 1.f);
+    } else {
+      asm volatile("" : "+s"(n), "+s"(lg_cp));
+      transform(data, tw, p, n, lg_cp, 1.f);
+      asm volatile("" : "+s"(n), "+s"(lg_cp));
+    }
+    asm volatile("" : "+v"(tid));
+    // Eq. 5: each thread adds up the squares of whole rows (all CP sequences of a token), the
+    // sequences visited in an order rotated by the lane so that neighbours start on other banks
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int e = threadIdx.x + i * kFreqThreads;
-      float sq = 0.f;
-      if (e < elems) {
-        const float2 x = data[phys(e >> lg_cp, e & (cp - 1), lg_cp)];
-        sq = x.x * x.x + x.y * x.y;
+    for (int i = 0; i < ROWS; ++i) {
+      const int row = tid + i * kFreqThreads;
+      if (row < n) {
+        const float2* line = data + phys(row, 0, lg_cp);
+        float sq = 0.f;
+        for (int q = 0; q < cp; ++q) {
+          const float2 x = line[(q + tid) & (cp - 1)];
+          sq = fmaf(x.x, x.x, fmaf(x.y, x.y, sq));
+        }
+        acc[i] += sq;
       }
-      for (int off = 1; off < cp; off <<= 1) sq += __shfl_xor(sq, off, 64);
-      acc[i] += sq;
     }
     __syncthreads();
   }
   float* out = partial + ((int64_t)tensor * p.groups + g) * n;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int e = threadIdx.x + i * kFreqThreads;
-    if (e < elems && (e & (cp - 1)) == 0) out[e >> lg_cp] = acc[i];
+  for (int i = 0; i < ROWS; ++i) {
+    const int row = threadIdx.x + i * kFreqThreads;
+    if (row < n) out[row] = acc[i];
   }
 }
 
@@ -327,15 +386,28 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float* __restrict__ sc
       if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (tid == 0) {
-      uint32_t left = need;
-      int bin = 255;
-      for (; bin > 0; --bin) {
-        if (hist[bin] >= left) break;
-        left -= hist[bin];
+    if (tid < 64) {
+      // the first wave walks the histogram from the top: lane l owns bins 4l .. 4l+3; a suffix
+      // scan over the lanes gives the count above each lane's bins, and the one lane whose bins
+      // take the running count to `need` publishes the bin and what is left to take inside it
+      const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+      const uint32_t tot = h0 + h1 + h2 + h3;
+      uint32_t incl = tot;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t y = __shfl_down(incl, off, 64);
+        if (tid + off < 64) incl += y;
       }
-      sh_prefix = prefix | ((uint32_t)bin << shift);
-      sh_need = left;
+      uint32_t above = incl - tot;
+      if (above < need && need <= above + tot) {
+        int bin = 4 * tid + 3;
+        uint32_t left = need - above;
+        if (h3 < left) { left -= h3; bin = 4 * tid + 2;
+          if (h2 < left) { left -= h2; bin = 4 * tid + 1;
+            if (h1 < left) { left -= h1; bin = 4 * tid; } } }
+        sh_prefix = prefix | ((uint32_t)bin << shift);
+        sh_need = left;
+      }
     }
     __syncthreads();
     prefix = sh_prefix;
@@ -404,15 +476,15 @@ static bool make_plan(int32_t n, int32_t row_elems, double alpha, int32_t n_batc
   if (c > bins) c = bins;
   p->cutoff = c;
   p->strips = row_elems / (2 << lg);
-  // enough workgroups to fill the chip twice over, no more than one per strip
-  int groups = p->strips;
-  while (groups % 2 == 0 && (int64_t)n_batch * 2 * (groups / 2) >= 512) groups /= 2;
-  p->groups = groups;
+  // one strip per workgroup.  The split depends on the shape alone, not on the batch, so that a
+  // sequence gets the same bits whatever it is batched with.
+  (void)n_batch;
+  p->groups = p->strips;
   return true;
 }
 
-static size_t freq_lds_bytes(const FftPlan& p) {
-  return ((size_t)((p.n + (p.n >> 4) + 1) << p.lg_cp) + (size_t)(p.n + 1) / 2) * sizeof(float2);
+static size_t freq_lds_bytes(const FftPlan& p, bool fixed) {
+  return ((size_t)((p.n + (p.n >> 4) + 1) << p.lg_cp) + (size_t)(fixed ? p.n / 8 : (p.n + 1) / 2)) * sizeof(float2);
 }
 
 }  // namespace ct
@@ -449,16 +521,26 @@ ct_status ct_frequency_scores(const void* k, const void* v, int32_t n_batch, int
   if (workspace == nullptr || workspace_bytes < need)
     return fail(CT_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
   hipStream_t s = (hipStream_t)stream;
-  const size_t lds = freq_lds_bytes(p);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)freq_energy_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(freq_energy_kernel)");
-    attr_set = true;
+  // power-of-two lengths from 256 on whose strips hold the full kFreqMaxElems values take the kernel
+  // with the plan compiled in; everything else the one that reads the plan at run time
+  using Kernel = void (*)(const uint16_t*, const uint16_t*, int64_t, int32_t, int32_t, FftPlan, float*);
+  Kernel kern = freq_energy_kernel<0>;
+  if ((int64_t)n_tokens << p.lg_cp == kFreqMaxElems) {
+    switch (n_tokens) {
+      case 256: kern = freq_energy_kernel<256>; break;
+      case 512: kern = freq_energy_kernel<512>; break;
+      case 1024: kern = freq_energy_kernel<1024>; break;
+      case 2048: kern = freq_energy_kernel<2048>; break;
+      case 4096: kern = freq_energy_kernel<4096>; break;
+      default: break;
+    }
   }
+  const size_t lds = freq_lds_bytes(p, kern != freq_energy_kernel<0>);
+  hipError_t ea = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (ea != hipSuccess) return hip_fail(ea, "hipFuncSetAttribute(freq_energy_kernel)");
   const int n_work = n_batch * 2 * p.groups;
   int slot = prof_begin(KC_FREQ, s);
-  hipLaunchKernelGGL(freq_energy_kernel, dim3(n_work), dim3(kFreqThreads), lds, s, (const uint16_t*)k, (const uint16_t*)v,
+  hipLaunchKernelGGL(kern, dim3(n_work), dim3(kFreqThreads), lds, s, (const uint16_t*)k, (const uint16_t*)v,
                      batch_stride, row_elems, n_work, p, (float*)workspace);
   const int64_t total = (int64_t)n_batch * n_tokens;
   hipLaunchKernelGGL(freq_finish_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float*)workspace,
