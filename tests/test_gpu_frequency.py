@@ -144,3 +144,35 @@ def test_selection_end_to_end(n, row, n_batch, ratio):
                   f"{undecided} tokens within the score tolerance of the threshold", flush=True)
         else:
             assert np.array_equal(g, np.arange(n))
+
+
+def test_bench_shape_all_layers_of_a_chunk():
+    """The launch `bench.py --offline-select` times: 32 layers of a 2048-token chunk in one call
+    (four distinct synthetic layers, repeated), every score and every index set checked."""
+    n, row, n_batch, alpha, ratio = 2048, 1024, 32, 0.5, 0.15
+    say(f"select_frequency bench shape n={n} row={row} batch={n_batch}")
+    kb, vb = W.make_spectral_kv(1006, n, row, 4)
+    k = dev_bf16(kb).repeat(8, 1, 1).contiguous()
+    v = dev_bf16(vb).repeat(8, 1, 1).contiguous()
+    n_sel = B.ct_frequency_n_selected(n, ratio)
+    ws_bytes = B.ct_frequency_workspace_bytes(n_batch, n, row)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    scores = torch.empty((n_batch, n), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n_batch, n_sel), dtype=torch.int32, device="cuda")
+    B.ct_select_frequency(k, v, n_batch, n * row, n, row, alpha, ratio, idx, scores, ws, ws_bytes)
+    torch.cuda.synchronize()
+    got_s, got_i = scores.cpu().numpy(), idx.cpu().numpy()
+    worst = 0.0
+    for b in range(4):
+        want_i, want_s = O.select_frequency(W.bf16_bits_to_f64(kb[b]), W.bf16_bits_to_f64(vb[b]), alpha, ratio)
+        tol = SCORE_REL * want_s.max()
+        tau = np.sort(want_s)[::-1][n_sel - 1]
+        for rep in range(8):
+            s, g = got_s[b + 4 * rep], got_i[b + 4 * rep]
+            worst = max(worst, np.abs(s - want_s).max() / want_s.max())
+            assert np.abs(s - want_s).max() <= tol
+            assert np.array_equal(s, got_s[b])                                   # same input, same bits
+            assert np.array_equal(g, O.topk_indices(s, n_sel))
+            assert np.isin(np.nonzero(want_s > tau + 2 * tol)[0], g).all()
+            assert not np.isin(np.nonzero(want_s < tau - 2 * tol)[0], g).any()
+    print(f"[parity] bench-shape scores: worst error {worst:.2e} of the largest score (<= {SCORE_REL:g})", flush=True)
