@@ -19,7 +19,8 @@
 // Workgroup: 512 threads = 8 waves (2 feature halves x 4 token quarters), tile 256 features x
 // 256 tokens x 64 (K step), wave tile 128 x 64 = 4 x 2 MFMA tiles of
 // v_mfma_f32_32x32x16_bf16, three weight-tile and two token-tile LDS slots of 32 KiB (loads run
-// two and one K steps ahead), one barrier per K step.  Two waves share a SIMD, so one wave's
+// two and one K steps ahead), one barrier per K step, placed before the step's last MFMA group so
+// that it passes while the matrix core is busy.  Two waves share a SIMD, so one wave's other
 // waits hide behind the other's MFMAs.
 // Workgroups are numbered so that the ones resident on one XCD (ids congruent mod 8) cover a
 // patch of neighbouring tiles and share their W and X tiles in that XCD's L2.
@@ -38,8 +39,6 @@ constexpr int BK = 64;            // reduction elements per stage
 constexpr int ROWB = BK * 2;      // LDS row in bytes (unpadded, swizzled)
 constexpr int A_BYTES = BF * ROWB;
 constexpr int A_SLOTS = 3, B_SLOTS = 2;   // LDS slots per operand tile
-constexpr int NWAVES = 8;
-constexpr int A_LOADS = BF / 8 / NWAVES;   // wave-wide loads (8 rows each) per wave and stage
 
 enum Epilogue { EPI_QKV_ROPE = 0, EPI_LINEAR = 1, EPI_SWIGLU = 2 };
 
@@ -76,9 +75,12 @@ __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 // EPI_SWIGLU: the 128 A rows of a wave are 64 gate rows followed by the 64 up rows of the same
 // output features, so gate and up of one (feature, token) land in the same lane and register
 // index of accumulator tiles (m, m + 2) - the same pairing the half-split RoPE uses.
-template <int EPI, int D, int STYLE, int NB>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_kernel(GemmArgs a, RopeTable rope,
-                                                                                             ChunkTable chunks) {
+template <int EPI, int D, int STYLE, int NB, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void gemm_kernel(
+    GemmArgs a, RopeTable rope, ChunkTable chunks) {
+  constexpr int NWAVES = NW;                 // 8: two waves per SIMD, wave tile 128 x 32 NB; 4: one, 128 x 64 NB
+  constexpr int A_LOADS = BF / 8 / NWAVES;   // wave-wide loads (8 rows each) per wave and stage
+  constexpr int TW = 8 * NB / NW;            // 32-token MFMA tiles per wave
   constexpr int BT = 128 * NB;
   constexpr int B_BYTES = BT * ROWB;
   constexpr int B_LOADS = BT / 8 / NWAVES;
@@ -156,23 +158,29 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
   for (int ks = 0; ks < BK / 16; ++ks) {
     a_frag[ks] = (wf * 128 + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
-    b_frag[ks] = (wt * 32 * NB + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
+    b_frag[ks] = (wt * 32 * TW + l32) * ROWB + (((2 * ks + hi) ^ swz(l32)) * 16);
   }
 
-  f32x16 acc[4][NB];
+  f32x16 acc[4][TW];
 #pragma unroll
   for (int m = 0; m < 4; ++m)
 #pragma unroll
-    for (int n = 0; n < NB; ++n)
+    for (int n = 0; n < TW; ++n)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
 
   // Pipeline.  The weight tile of K step kt + 2 and the token tile of step kt + 1 are in flight
   // while step kt is multiplied (all 160 KiB of LDS: 3 + 2 slots of 32 KiB); with one step in
   // flight the load path alone (issue, L2 latency, barrier) takes as long as the MFMAs of a step.
-  // Loads are issued in the order B(kt + 1), A(kt + 2), so at the top of step kt everything but
-  // the newest A_LOADS loads - A(kt + 1) - is waited for.  Past the end the last step is loaded
-  // again into the free slots, which keeps the number of loads in flight, and the wait, uniform.
+  // Loads are issued in the order B(kt + 1), A(kt + 2), so when step kt + 1 is about to start
+  // everything but the newest A_LOADS loads - A(kt + 2) - is waited for.  Past the end the last
+  // step is loaded again into the free slots, which keeps the number of loads in flight, and the
+  // wait, uniform.
+  // The workgroup barrier of a step sits before its last MFMA group, not after it: a wave waits
+  // for its loads of the next step, meets the others, issues the first fragment reads of the
+  // next step and only then issues the last 4 x TW MFMAs of this step, so the barrier and the
+  // LDS latency that follows it pass while the matrix core still has work queued.  (All waves of
+  // a workgroup stand at the barrier together, so the other wave of the SIMD cannot cover it.)
   const int nk = a.E / BK;
   constexpr int WAIT_STEP = (A_LOADS & 15) | 0x0f70;   // s_waitcnt vmcnt(A_LOADS)
   __builtin_amdgcn_s_waitcnt(0x0f70);   // ordinary loads so far (row indices) are complete
@@ -180,40 +188,51 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   issue_b(0, 0, 0); issue_b(0, 0, 1);
   issue_a(min(1, nk - 1) * BK, 1, 0); issue_a(min(1, nk - 1) * BK, 1, 1);
   int sa = 0, sb = 0;
+  // The fragment reads of MFMA group ks + 1 are issued before the MFMAs of group ks (two register
+  // sets), so a wave waits for LDS once per K step instead of once per group.
+  bf16x8 fa[2][4], fb[2][TW];
+  auto read_frags = [&](const unsigned char* a_base, const unsigned char* b_base, int ks, int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int n = 0; n < TW; ++n) fb[set][n] = *reinterpret_cast<const bf16x8*>(b_base + b_frag[ks] + n * 32 * ROWB);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) fa[set][m] = *reinterpret_cast<const bf16x8*>(a_base + a_frag[ks] + m * 32 * ROWB);
+  };
+  auto mfma_group = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int n = 0; n < TW; ++n)
+        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][m], fb[set][n], acc[m][n], 0, 0, 0);
+  };
+  __builtin_amdgcn_s_waitcnt(WAIT_STEP);   // this wave's loads of step 0 have landed
+  __syncthreads();                         // everybody's have
+  read_frags(lds, lds + A_SLOTS * A_BYTES, 0, 0);
   for (int kt = 0; kt < nk; ++kt) {
-    __builtin_amdgcn_s_waitcnt(WAIT_STEP);   // this wave's loads of step kt have landed
-    __syncthreads();                         // everybody's have; everybody is done with step kt - 1
     const unsigned char* a_base = lds + sa * A_BYTES;
     const unsigned char* b_base = lds + A_SLOTS * A_BYTES + sb * B_BYTES;
     const int sa_free = sa == 0 ? A_SLOTS - 1 : sa - 1;   // slot of step kt - 1
     const int sb_free = sb ^ 1;
+    const int sa_next = sa == A_SLOTS - 1 ? 0 : sa + 1;
     const int kb1 = min(kt + 1, nk - 1) * BK, ka2 = min(kt + 2, nk - 1) * BK;
-    // The fragment reads of MFMA group ks + 1 are issued before the MFMAs of group ks (two
-    // register sets), so a wave waits for LDS once per K step instead of once per group.
-    bf16x8 fa[2][4], fb[2][NB];
-    auto read_frags = [&](int ks, int set) __attribute__((always_inline)) {
 #pragma unroll
-      for (int n = 0; n < NB; ++n) fb[set][n] = *reinterpret_cast<const bf16x8*>(b_base + b_frag[ks] + n * 32 * ROWB);
-#pragma unroll
-      for (int m = 0; m < 4; ++m) fa[set][m] = *reinterpret_cast<const bf16x8*>(a_base + a_frag[ks] + m * 32 * ROWB);
-    };
-    read_frags(0, 0);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      // the loads go out a quarter at a time, one quarter per MFMA group: a burst of all of them
-      // from all eight waves would queue at the texture addresser
-      if (ks < 2) issue_b(kb1, sb_free, ks);
-      else issue_a(ka2, sa_free, ks - 2);
-      if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+    for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+      // the loads go out a part at a time, one part per MFMA group: a burst of all of them from
+      // all waves would queue at the texture addresser.  B first: it is needed a step earlier.
+      if (ks == 0) { issue_b(kb1, sb_free, 0); issue_b(kb1, sb_free, 1); }
+      else issue_a(ka2, sa_free, ks - 1);
+      read_frags(a_base, b_base, ks + 1, (ks + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int m = 0; m < 4; ++m)
-#pragma unroll
-        for (int n = 0; n < NB; ++n)
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][m], fb[ks & 1][n], acc[m][n], 0, 0, 0);
+      mfma_group(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    sa = sa == A_SLOTS - 1 ? 0 : sa + 1;
+    __builtin_amdgcn_s_waitcnt(WAIT_STEP & ~0x0f00);   // vmcnt(A_LOADS): this wave's loads of step kt + 1 have
+                                                        // landed; lgkmcnt(0): its fragment reads of step kt are done
+    __syncthreads();                         // everybody's have; everybody is done reading step kt
+    read_frags(lds + sa_next * A_BYTES, lds + A_SLOTS * A_BYTES + sb_free * B_BYTES, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group((BK / 16 - 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    sa = sa_next;
     sb = sb_free;
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);   // the repeated loads of the last steps have landed before the LDS is released
@@ -223,8 +242,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if constexpr (EPI == EPI_LINEAR) {
     const int f0 = f_blk + wf * 128;
 #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-      const int t = t_blk + wt * 32 * NB + n * 32 + l32;
+    for (int n = 0; n < TW; ++n) {
+      const int t = t_blk + wt * 32 * TW + n * 32 + l32;
       if (t >= a.n_sel) continue;
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
@@ -249,8 +268,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   } else if constexpr (EPI == EPI_SWIGLU) {
     const int f0 = f_blk + wf * 64;          // output features of this wave: f0 .. f0 + 63
 #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-      const int t = t_blk + wt * 32 * NB + n * 32 + l32;
+    for (int n = 0; n < TW; ++n) {
+      const int t = t_blk + wt * 32 * TW + n * 32 + l32;
       if (t >= a.n_sel) continue;
 #pragma unroll
       for (int m = 0; m < 2; ++m) {          // gate tile m, up tile m + 2
@@ -279,8 +298,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int rope_end = (a.Hq + a.Hkv) * D;   // features below this are q or k heads
     const int q_end = a.Hq * D;
   #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-      const int t = t_blk + wt * 32 * NB + n * 32 + l32;
+    for (int n = 0; n < TW; ++n) {
+      const int t = t_blk + wt * 32 * TW + n * 32 + l32;
       const bool t_ok = t < a.n_sel;
       const int tc = t_ok ? t : a.n_sel - 1;
       const int32_t pos = a.sel_pos ? a.sel_pos[tc] : position_of_row(chunks, a.sel_idx[tc]);
@@ -376,17 +395,25 @@ static int pick_nb(const GemmArgs& a, bool swiglu) {
 }
 
 template <typename Kernel>
-static ct_status launch_gemm(Kernel kernel, const GemmArgs& a, const RopeTable& rope, const ChunkTable& tab,
+static ct_status launch_gemm(Kernel kernel, int threads, const GemmArgs& a, const RopeTable& rope, const ChunkTable& tab,
                              KernelClass kc, hipStream_t s) {
   const int total = a.nF * a.nT;
   const int per_xcd = (total + 7) / 8;
-  dim3 grid(per_xcd * 8), block(512);
+  dim3 grid(per_xcd * 8), block(threads);
   int slot = prof_begin(kc, s);
   hipLaunchKernelGGL(kernel, grid, block, 0, s, a, rope, tab);
   prof_end(kc, slot, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "gemm kernel launch");
   return CT_OK;
+}
+
+template <int EPI, int D, int STYLE, int NB>
+static ct_status launch_variant(const GemmArgs& a, const RopeTable& rope, const ChunkTable& tab, KernelClass kc,
+                                hipStream_t s) {
+  // Eight waves.  Four (one per SIMD, 128 x 128 wave tiles, half the LDS reads per MFMA) compile
+  // from the same source and were measured: no faster on any layer shape.
+  return launch_gemm(gemm_kernel<EPI, D, STYLE, NB, 8>, 512, a, rope, tab, kc, s);
 }
 
 ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
@@ -424,16 +451,16 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
   }
   if (nb == 2) {
     if (cfg->head_dim == 128)
-      return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0, 2>, a, rope, tab, KC_QKV, s)
-                                  : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1, 2>, a, rope, tab, KC_QKV, s);
-    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0, 2>, a, rope, tab, KC_QKV, s)
-                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1, 2>, a, rope, tab, KC_QKV, s);
+      return cfg->rope_style == 0 ? launch_variant<EPI_QKV_ROPE, 128, 0, 2>(a, rope, tab, KC_QKV, s)
+                                  : launch_variant<EPI_QKV_ROPE, 128, 1, 2>(a, rope, tab, KC_QKV, s);
+    return cfg->rope_style == 0 ? launch_variant<EPI_QKV_ROPE, 64, 0, 2>(a, rope, tab, KC_QKV, s)
+                                : launch_variant<EPI_QKV_ROPE, 64, 1, 2>(a, rope, tab, KC_QKV, s);
   }
   if (cfg->head_dim == 128)
-    return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 0, 1>, a, rope, tab, KC_QKV, s)
-                                : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 128, 1, 1>, a, rope, tab, KC_QKV, s);
-  return cfg->rope_style == 0 ? launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 0, 1>, a, rope, tab, KC_QKV, s)
-                              : launch_gemm(gemm_kernel<EPI_QKV_ROPE, 64, 1, 1>, a, rope, tab, KC_QKV, s);
+    return cfg->rope_style == 0 ? launch_variant<EPI_QKV_ROPE, 128, 0, 1>(a, rope, tab, KC_QKV, s)
+                                : launch_variant<EPI_QKV_ROPE, 128, 1, 1>(a, rope, tab, KC_QKV, s);
+  return cfg->rope_style == 0 ? launch_variant<EPI_QKV_ROPE, 64, 0, 1>(a, rope, tab, KC_QKV, s)
+                              : launch_variant<EPI_QKV_ROPE, 64, 1, 1>(a, rope, tab, KC_QKV, s);
 }
 
 ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
@@ -454,8 +481,8 @@ ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void*
   memset(&rope, 0, sizeof(rope));
   ChunkTable tab;
   memset(&tab, 0, sizeof(tab));
-  return nb == 2 ? launch_gemm(gemm_kernel<EPI_LINEAR, 128, 0, 2>, a, rope, tab, KC_LINEAR, s)
-                 : launch_gemm(gemm_kernel<EPI_LINEAR, 128, 0, 1>, a, rope, tab, KC_LINEAR, s);
+  return nb == 2 ? launch_variant<EPI_LINEAR, 128, 0, 2>(a, rope, tab, KC_LINEAR, s)
+                 : launch_variant<EPI_LINEAR, 128, 0, 1>(a, rope, tab, KC_LINEAR, s);
 }
 
 ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
@@ -476,8 +503,8 @@ ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void*
   memset(&rope, 0, sizeof(rope));
   ChunkTable tab;
   memset(&tab, 0, sizeof(tab));
-  return nb == 2 ? launch_gemm(gemm_kernel<EPI_SWIGLU, 128, 0, 2>, a, rope, tab, KC_LINEAR, s)
-                 : launch_gemm(gemm_kernel<EPI_SWIGLU, 128, 0, 1>, a, rope, tab, KC_LINEAR, s);
+  return nb == 2 ? launch_variant<EPI_SWIGLU, 128, 0, 2>(a, rope, tab, KC_LINEAR, s)
+                 : launch_variant<EPI_SWIGLU, 128, 0, 1>(a, rope, tab, KC_LINEAR, s);
 }
 
 }  // namespace ct
