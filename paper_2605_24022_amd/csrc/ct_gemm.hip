@@ -241,6 +241,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
   // accumulator element i of tile (m, n): row f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
   if constexpr (EPI == EPI_LINEAR) {
     const int f0 = f_blk + wf * 128;
+    // All residual values of the wave's tile are fetched before the first result is stored: `out`
+    // may be the residual buffer itself, so the compiler cannot move these loads above stores on
+    // its own, and with four loads in flight per lane the epilogue is bound by memory latency.
+    u32x2 res[TW][4][4];
+    if (a.residual != nullptr) {
+#pragma unroll
+      for (int n = 0; n < TW; ++n) {
+        const int t = min(t_blk + wt * 32 * TW + n * 32 + l32, a.n_sel - 1);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const int fm = min(f0 + m * 32, a.O - 32);
+          const size_t row = (size_t)t * a.O + fm + 4 * hi;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) res[n][m][g] = *reinterpret_cast<const u32x2*>(a.residual + row + 8 * g);
+        }
+      }
+    }
 #pragma unroll
     for (int n = 0; n < TW; ++n) {
       const int t = t_blk + wt * 32 * TW + n * 32 + l32;
@@ -254,7 +271,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         for (int g = 0; g < 4; ++g) {
           float v0 = acc[m][n][4 * g + 0], v1 = acc[m][n][4 * g + 1], v2 = acc[m][n][4 * g + 2], v3 = acc[m][n][4 * g + 3];
           if (a.residual != nullptr) {
-            const u32x2 r = *reinterpret_cast<const u32x2*>(a.residual + row + 8 * g);
+            const u32x2 r = res[n][m][g];
             v0 += bf16_lo(r[0]); v1 += bf16_hi(r[0]); v2 += bf16_lo(r[1]); v3 += bf16_hi(r[1]);
           }
           u32x2 w;
