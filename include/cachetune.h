@@ -189,6 +189,17 @@ ct_status ct_rmsnorm(const void* x, const void* weight, float eps, int32_t n_tok
 ct_status ct_linear(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out, const void* residual,
                     void* out, void* stream);
 
+/* ct_linear with scratch memory.  When the 256 x 256 output tiles do not fill the last round over
+ * the compute units (say 320 tiles on 256 units), the tiles of that round are each computed by
+ * several workgroups that split the reduction, as fp32 partial tiles in `workspace`, and a second
+ * kernel adds the parts and the residual before the one rounding to bf16.  Same result layout
+ * and rounding as ct_linear; sums are formed in a different order.
+ *   workspace  device memory, 16-byte aligned, ct_linear_workspace_bytes() bytes (less, or NULL,
+ *              is legal: the call then behaves like ct_linear). */
+ct_status ct_linear_ws(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out,
+                       const void* residual, void* out, void* workspace, size_t workspace_bytes, void* stream);
+size_t ct_linear_workspace_bytes(int32_t n_tokens, int32_t k_len, int32_t n_out);
+
 /* out[t,:] = silu(x[t,:] * w_gate^T) * (x[t,:] * w_up^T) (SwiGLU), one kernel, bf16 result.
  *   w_gate, w_up device bf16 [n_out, k_len]; out device bf16 [n_tokens, n_out]. */
 ct_status ct_swiglu(const void* x, int32_t n_tokens, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,

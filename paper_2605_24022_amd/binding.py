@@ -24,7 +24,7 @@ EXPORTS = [
     "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
     "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
-    "ct_rmsnorm", "ct_linear", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
+    "ct_rmsnorm", "ct_linear", "ct_linear_ws", "ct_linear_workspace_bytes", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
     "ct_measure_mfma_rate", "ct_layer_latency_model", "ct_ratio_prior", "ct_ratio_search",
     "ct_frequency_scores", "ct_frequency_workspace_bytes", "ct_topk_indices", "ct_frequency_n_selected",
     "ct_select_frequency",
@@ -80,6 +80,9 @@ def load() -> ctypes.CDLL:
                                              P, P, P, P, c_size_t, P, P]
     lib.ct_rmsnorm.argtypes = [P, P, c_float, c_int32, c_int32, P, P]
     lib.ct_linear.argtypes = [P, c_int32, c_int32, P, c_int32, P, P, P]
+    lib.ct_linear_ws.argtypes = [P, c_int32, c_int32, P, c_int32, P, P, P, c_size_t, P]
+    lib.ct_linear_workspace_bytes.argtypes = [c_int32, c_int32, c_int32]
+    lib.ct_linear_workspace_bytes.restype = c_size_t
     lib.ct_swiglu.argtypes = [P, c_int32, c_int32, P, P, c_int32, P, P]
     lib.ct_partial_prefill_stack.argtypes = [cfgp, c_int32, c_float, POINTER(LayerWeights), c_int32, c_int32, P, P,
                                              c_int32, c_double, P, P, P, c_size_t, P, P]
@@ -115,7 +118,7 @@ def load() -> ctypes.CDLL:
     lib.ct_version.restype = c_char_p
     for name in ("ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
                  "ct_partial_prefill_layer", "ct_validate_indices", "ct_profile_read", "ct_rmsnorm", "ct_linear",
-                 "ct_swiglu", "ct_partial_prefill_stack"):
+                 "ct_linear_ws", "ct_swiglu", "ct_partial_prefill_stack"):
         getattr(lib, name).restype = c_int32
     _lib = lib
     return lib
@@ -224,6 +227,15 @@ def ct_rmsnorm(x, weight, eps, n_tokens, width, out, stream=None) -> None:
 
 def ct_linear(x, n_tokens, k_len, w, n_out, residual, out, stream=None) -> None:
     _check(load().ct_linear(_ptr(x), n_tokens, k_len, _ptr(w), n_out, _ptr(residual), _ptr(out), _stream(stream)))
+
+
+def ct_linear_workspace_bytes(n_tokens, k_len, n_out) -> int:
+    return int(load().ct_linear_workspace_bytes(n_tokens, k_len, n_out))
+
+
+def ct_linear_ws(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, stream=None) -> None:
+    _check(load().ct_linear_ws(_ptr(x), n_tokens, k_len, _ptr(w), n_out, _ptr(residual), _ptr(out), _ptr(workspace),
+                               workspace_bytes, _stream(stream)))
 
 
 def ct_swiglu(x, n_tokens, k_len, w_gate, w_up, n_out, out, stream=None) -> None:

@@ -182,7 +182,7 @@ static const void* device_view_of_host(const void* p) {
 // Workgroups (of 1024 threads) of the stream-in kernel.  Eight keep the host link at about 55 GB/s
 // on MI355X (four: 45 GB/s); every further one takes a compute unit away from the kernels of the recompute
 // stream and slows them more than the faster transfer gains.
-static int stream_in_blocks() {
+int stream_in_blocks() {
   static const int v = []() {
     const char* e = getenv("CT_STREAM_IN_BLOCKS");
     const int n = e != nullptr ? atoi(e) : 0;

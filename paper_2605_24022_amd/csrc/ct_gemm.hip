@@ -40,7 +40,7 @@ constexpr int ROWB = BK * 2;      // LDS row in bytes (unpadded, swizzled)
 constexpr int A_BYTES = BF * ROWB;
 constexpr int A_SLOTS = 3, B_SLOTS = 2;   // LDS slots per operand tile
 
-enum Epilogue { EPI_QKV_ROPE = 0, EPI_LINEAR = 1, EPI_SWIGLU = 2 };
+enum Epilogue { EPI_QKV_ROPE = 0, EPI_LINEAR = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 };
 
 struct GemmArgs {
   const uint16_t* hidden;        // B operand X [*, E], token major
@@ -49,6 +49,10 @@ struct GemmArgs {
   const uint16_t* w_up;          // SwiGLU only: the up matrix [O, E]
   int32_t n_sel, E, O;           // tokens, reduction length, features (rows of W)
   int32_t nF, nT;                // tiles
+  // this launch covers tiles v_begin .. v_begin + v_count - 1 (in the patch order below), each by
+  // k_parts workgroups that take consecutive parts of the reduction (k_parts > 1: EPI_PARTIAL)
+  int32_t v_begin, v_count, k_parts;
+  float* partial;                // EPI_PARTIAL: fp32 [v_count * k_parts][256 tokens][256 features]
   // EPI_QKV_ROPE
   const int32_t* sel_pos;
   const int32_t* sel_idx;
@@ -72,6 +76,20 @@ __device__ __forceinline__ int32_t position_of_row(const ChunkTable& tab, int32_
 // swizzle of the 16-byte pieces of LDS row r (rows are 128 bytes: two rows per 256-byte bank span)
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 
+// Tile number -> (feature tile, token tile): tiles are numbered patch by patch (4 feature tiles x
+// 8 token tiles), so that the workgroups resident on one XCD cover neighbouring tiles.
+__device__ __forceinline__ void tile_of(int v, int nF, int nT, int* f_tile, int* t_tile) {
+  constexpr int PF = 4, PT = 8;
+  const int tp = v / (PT * nF);
+  const int rem = v - tp * PT * nF;
+  const int th = min(PT, nT - tp * PT);
+  const int fp = rem / (PF * th);
+  const int r2 = rem - fp * PF * th;
+  const int fw = min(PF, nF - fp * PF);
+  *f_tile = fp * PF + r2 % fw;
+  *t_tile = tp * PT + r2 / fw;
+}
+
 // EPI_SWIGLU: the 128 A rows of a wave are 64 gate rows followed by the 64 up rows of the same
 // output features, so gate and up of one (feature, token) land in the same lane and register
 // index of accumulator tiles (m, m + 2) - the same pairing the half-split RoPE uses.
@@ -90,19 +108,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
   const int l32 = lane & 31, hi = lane >> 5;
 
   // ---- workgroup -> tile, XCD aware (consecutive ids go to different XCDs) ----------------
-  const int total = a.nF * a.nT;
-  const int per_xcd = (total + 7) / 8;
-  const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (v >= total) return;
-  constexpr int PF = 4, PT = 8;
-  const int tp = v / (PT * a.nF);
-  const int rem = v - tp * PT * a.nF;
-  const int th = min(PT, a.nT - tp * PT);
-  const int fp = rem / (PF * th);
-  const int r2 = rem - fp * PF * th;
-  const int fw = min(PF, a.nF - fp * PF);
-  const int f_blk = (fp * PF + r2 % fw) * (EPI == EPI_SWIGLU ? BF / 2 : BF);   // first output feature
-  const int t_blk = (tp * PT + r2 / fw) * BT;
+  const int items = a.v_count * a.k_parts;
+  const int per_xcd = (items + 7) / 8;
+  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (item >= items) return;
+  const int kp = item % a.k_parts;
+  int f_tile, t_tile;
+  tile_of(a.v_begin + item / a.k_parts, a.nF, a.nT, &f_tile, &t_tile);
+  const int f_blk = f_tile * (EPI == EPI_SWIGLU ? BF / 2 : BF);   // first output feature
+  const int t_blk = t_tile * BT;
 
   // ---- global -> LDS loads -------------------------------------------------------------------
   // load j of this wave fills LDS rows (NWAVES * j + wave) * 8 .. + 7 of the A (or B) tile; this
@@ -181,12 +195,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
   // next step and only then issues the last 4 x TW MFMAs of this step, so the barrier and the
   // LDS latency that follows it pass while the matrix core still has work queued.  (All waves of
   // a workgroup stand at the barrier together, so the other wave of the SIMD cannot cover it.)
-  const int nk = a.E / BK;
+  // this workgroup's part of the reduction: K steps kbeg .. kbeg + nk - 1
+  const int nk_all = a.E / BK;
+  const int kbeg = (int)((long)kp * nk_all / a.k_parts);
+  const int nk = (int)((long)(kp + 1) * nk_all / a.k_parts) - kbeg;
+  const int kbase = kbeg * BK;
   constexpr int WAIT_STEP = (A_LOADS & 15) | 0x0f70;   // s_waitcnt vmcnt(A_LOADS)
   __builtin_amdgcn_s_waitcnt(0x0f70);   // ordinary loads so far (row indices) are complete
-  issue_a(0, 0, 0); issue_a(0, 0, 1);
-  issue_b(0, 0, 0); issue_b(0, 0, 1);
-  issue_a(min(1, nk - 1) * BK, 1, 0); issue_a(min(1, nk - 1) * BK, 1, 1);
+  issue_a(kbase, 0, 0); issue_a(kbase, 0, 1);
+  issue_b(kbase, 0, 0); issue_b(kbase, 0, 1);
+  issue_a(kbase + min(1, nk - 1) * BK, 1, 0); issue_a(kbase + min(1, nk - 1) * BK, 1, 1);
   int sa = 0, sb = 0;
   // The fragment reads of MFMA group ks + 1 are issued before the MFMAs of group ks (two register
   // sets), so a wave waits for LDS once per K step instead of once per group.
@@ -213,7 +231,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const int sa_free = sa == 0 ? A_SLOTS - 1 : sa - 1;   // slot of step kt - 1
     const int sb_free = sb ^ 1;
     const int sa_next = sa == A_SLOTS - 1 ? 0 : sa + 1;
-    const int kb1 = min(kt + 1, nk - 1) * BK, ka2 = min(kt + 2, nk - 1) * BK;
+    const int kb1 = kbase + min(kt + 1, nk - 1) * BK, ka2 = kbase + min(kt + 2, nk - 1) * BK;
 #pragma unroll
     for (int ks = 0; ks < BK / 16 - 1; ++ks) {
       // the loads go out a part at a time, one part per MFMA group: a burst of all of them from
@@ -239,7 +257,22 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 
   // ---- epilogues ---------------------------------------------------------------------------------
   // accumulator element i of tile (m, n): row f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
-  if constexpr (EPI == EPI_LINEAR) {
+  if constexpr (EPI == EPI_PARTIAL) {
+    // fp32 partial sums of this part of the reduction, token major inside the tile, 16-byte stores
+    float* dst = a.partial + (size_t)item * (BT * BF);
+#pragma unroll
+    for (int n = 0; n < TW; ++n) {
+      const int tl = wt * 32 * TW + n * 32 + l32;
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 w = {acc[m][n][4 * g + 0], acc[m][n][4 * g + 1], acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]};
+          *reinterpret_cast<f32x4*>(dst + (size_t)tl * BF + wf * 128 + m * 32 + 8 * g + 4 * hi) = w;
+        }
+    }
+    return;
+  } else if constexpr (EPI == EPI_LINEAR) {
     const int f0 = f_blk + wf * 128;
     // All residual values of the wave's tile are fetched before the first result is stored: `out`
     // may be the residual buffer itself, so the compiler cannot move these loads above stores on
@@ -390,11 +423,41 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
   }
 }
 
+// Sum of the k_parts partial tiles of EPI_PARTIAL (+ residual), rounded to bf16 and written to
+// out[t, f].  One thread per token and four consecutive features; a workgroup covers 4 tokens.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs a) {
+  const int tile_local = blockIdx.x >> 6;                 // 64 workgroups per 256 x 256 tile
+  const int tl = ((blockIdx.x & 63) << 2) + (threadIdx.x >> 6);
+  const int fl = (threadIdx.x & 63) << 2;
+  int f_tile, t_tile;
+  tile_of(a.v_begin + tile_local, a.nF, a.nT, &f_tile, &t_tile);
+  const int t = t_tile * 256 + tl, f = f_tile * BF + fl;
+  if (t >= a.n_sel || f >= a.O) return;
+  const float* src = a.partial + ((size_t)tile_local * a.k_parts * 256 + tl) * BF + fl;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(src);
+  for (int kp = 1; kp < a.k_parts; ++kp) {
+    const f32x4 p = *reinterpret_cast<const f32x4*>(src + (size_t)kp * (256 * BF));
+    sum += p;
+  }
+  const size_t o = (size_t)t * a.O + f;
+  if (a.residual != nullptr) {
+    const u32x2 r = *reinterpret_cast<const u32x2*>(a.residual + o);
+    sum[0] += bf16_lo(r[0]); sum[1] += bf16_hi(r[0]); sum[2] += bf16_lo(r[1]); sum[3] += bf16_hi(r[1]);
+  }
+  u32x2 w;
+  w[0] = pack_bf16(sum[0], sum[1]);
+  w[1] = pack_bf16(sum[2], sum[3]);
+  *reinterpret_cast<u32x2*>(a.out + o) = w;
+}
+
 }  // namespace
 
 static void fill_tiles(GemmArgs* a, bool swiglu, int nb) {
   a->nF = (a->O + (swiglu ? BF / 2 : BF) - 1) / (swiglu ? BF / 2 : BF);
   a->nT = (a->n_sel + 128 * nb - 1) / (128 * nb);
+  a->v_begin = 0;
+  a->v_count = a->nF * a->nT;
+  a->k_parts = 1;
 }
 
 // Token tile width for a launch: 256 tokens per workgroup unless the workgroups then fill the last
@@ -414,8 +477,8 @@ static int pick_nb(const GemmArgs& a, bool swiglu) {
 template <typename Kernel>
 static ct_status launch_gemm(Kernel kernel, int threads, const GemmArgs& a, const RopeTable& rope, const ChunkTable& tab,
                              KernelClass kc, hipStream_t s) {
-  const int total = a.nF * a.nT;
-  const int per_xcd = (total + 7) / 8;
+  const int items = a.v_count * a.k_parts;
+  const int per_xcd = (items + 7) / 8;
   dim3 grid(per_xcd * 8), block(threads);
   int slot = prof_begin(kc, s);
   hipLaunchKernelGGL(kernel, grid, block, 0, s, a, rope, tab);
@@ -480,8 +543,42 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
                               : launch_variant<EPI_QKV_ROPE, 64, 1, 1>(a, rope, tab, KC_QKV, s);
 }
 
+// The last round of 256-token tiles of a linear launch, when it would leave most compute units
+// idle, is run with the reduction of each tile split over several workgroups (fp32 partial tiles
+// in `ws`, then a small kernel that adds them, and the residual, and rounds).  Returns the number
+// of parts, or 1 when splitting is not worth it or `ws` is too small.
+static int split_plan(const GemmArgs& a256, size_t ws_bytes, double cost_unsplit, int n_cu, int* full_tiles) {
+  const int tiles = a256.nF * a256.nT;
+  const int rem = tiles % n_cu;
+  const int nk = a256.E / BK;
+  *full_tiles = tiles - rem;
+  if (rem == 0 || rem > n_cu / 2) return 1;
+  int parts = n_cu / rem;
+  if (parts > 8) parts = 8;
+  if (parts > nk / 8) parts = nk / 8;
+  if (parts < 2) return 1;
+  if (ws_bytes < (size_t)rem * parts * 256 * BF * sizeof(float)) return 1;
+  // in units of one round of 256-token tiles: the split round, plus the partial tiles' trip
+  // through memory and the two extra launches (measured: 0.45 of a round for 256 partial tiles at
+  // K = 4096, where a round takes 100 us; in proportion less for longer reductions)
+  const double cost = (double)(*full_tiles / n_cu) + 1.05 / parts + 0.45 * (64.0 / nk) * (rem * parts / 256.0);
+  return cost < cost_unsplit ? parts : 1;
+}
+
+size_t linear_workspace_bytes(int32_t n_tok, int32_t k_len, int32_t n_out) {
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n_sel = n_tok;
+  a.E = k_len;
+  a.O = n_out;
+  fill_tiles(&a, false, 2);
+  // at most one partial tile per compute unit, whatever share of the chip the launch is planned for
+  const int tiles = a.nF * a.nT;
+  return (size_t)(tiles < 256 ? tiles * 8 < 256 ? tiles * 8 : 256 : 256) * 256 * BF * sizeof(float);
+}
+
 ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
-                        void* out, hipStream_t s) {
+                        void* out, void* ws, size_t ws_bytes, int n_cu, hipStream_t s) {
   if (n_tok == 0) return CT_OK;
   GemmArgs a;
   memset(&a, 0, sizeof(a));
@@ -492,12 +589,40 @@ ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void*
   a.n_sel = n_tok;
   a.E = k_len;
   a.O = n_out;
-  const int nb = pick_nb(a, false);
-  fill_tiles(&a, false, nb);
   RopeTable rope;
   memset(&rope, 0, sizeof(rope));
   ChunkTable tab;
   memset(&tab, 0, sizeof(tab));
+  const int nb = pick_nb(a, false);
+  if (ws != nullptr) {
+    GemmArgs t2 = a, t1 = a;
+    fill_tiles(&t2, false, 2);
+    fill_tiles(&t1, false, 1);
+    if (n_cu <= 0 || n_cu > 256) n_cu = 256;
+    const double c2 = (double)((t2.nF * t2.nT + n_cu - 1) / n_cu), c1 = 0.56 * (double)((t1.nF * t1.nT + n_cu - 1) / n_cu);
+    int full = 0;
+    const int parts = split_plan(t2, ws_bytes, c1 < c2 ? c1 : c2, n_cu, &full);
+    if (parts > 1) {
+      ct_status st = CT_OK;
+      a = t2;
+      if (full > 0) {
+        a.v_count = full;
+        if ((st = launch_variant<EPI_LINEAR, 128, 0, 2>(a, rope, tab, KC_LINEAR, s)) != CT_OK) return st;
+      }
+      a.v_begin = full;
+      a.v_count = t2.nF * t2.nT - full;
+      a.k_parts = parts;
+      a.partial = static_cast<float*>(ws);
+      if ((st = launch_variant<EPI_PARTIAL, 128, 0, 2>(a, rope, tab, KC_LINEAR, s)) != CT_OK) return st;
+      int slot = prof_begin(KC_LINEAR, s);
+      hipLaunchKernelGGL(gemm_reduce_kernel, dim3(a.v_count * 64), dim3(256), 0, s, a);
+      prof_end(KC_LINEAR, slot, s);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return hip_fail(e, "gemm reduce launch");
+      return CT_OK;
+    }
+  }
+  fill_tiles(&a, false, nb);
   return nb == 2 ? launch_variant<EPI_LINEAR, 128, 0, 2>(a, rope, tab, KC_LINEAR, s)
                  : launch_variant<EPI_LINEAR, 128, 0, 1>(a, rope, tab, KC_LINEAR, s);
 }

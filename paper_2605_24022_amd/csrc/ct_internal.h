@@ -86,8 +86,14 @@ ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t*
                      const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
                      const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s);
 // out[t, :] = x[t, :] * w^T (+ residual[t, :]);  x [n_tok, k_len], w [n_out, k_len], bf16
+// ws (optional, linear_workspace_bytes() bytes): scratch that lets a launch whose last round of
+// workgroups would leave most compute units idle split the reduction of those tiles.  n_cu: the
+// compute units the launch can count on (256, less what a concurrent stream-in kernel holds).
 ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
-                        void* out, hipStream_t s);
+                        void* out, void* ws, size_t ws_bytes, int n_cu, hipStream_t s);
+// Workgroups of the kernel that streams host chunks in (each keeps a compute unit to itself).
+int stream_in_blocks();
+size_t linear_workspace_bytes(int32_t n_tok, int32_t k_len, int32_t n_out);
 // out[t, :] = silu(x[t, :] * w_gate^T) * (x[t, :] * w_up^T);  both weights [n_out, k_len]
 ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
                         void* out, hipStream_t s);

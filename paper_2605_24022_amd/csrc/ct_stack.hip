@@ -81,7 +81,7 @@ ct_status acquire_events(size_t n, std::vector<hipEvent_t>* out) {
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StackLayout {
-  size_t attn_ws, x_norm, q, k, v, attn_out, act, total;
+  size_t attn_ws, x_norm, q, k, v, attn_out, act, gemm_ws, gemm_ws_bytes, total;
 };
 
 StackLayout stack_layout(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx, int32_t n_sel) {
@@ -95,6 +95,11 @@ StackLayout stack_layout(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx
   L.v = off;        off += up256((size_t)n_sel * cfg->n_kv_heads * cfg->head_dim * 2);
   L.attn_out = off; off += up256((size_t)n_sel * cfg->n_q_heads * cfg->head_dim * 2);
   L.act = off;      off += up256((size_t)n_sel * ffn_dim * 2);
+  // scratch of the two linear launches (output projection, FFN down projection)
+  const size_t g1 = linear_workspace_bytes(n_sel, cfg->n_q_heads * cfg->head_dim, cfg->hidden);
+  const size_t g2 = linear_workspace_bytes(n_sel, ffn_dim, cfg->hidden);
+  L.gemm_ws_bytes = g1 > g2 ? g1 : g2;
+  L.gemm_ws = off;  off += up256(L.gemm_ws_bytes);
   L.total = off + 256;
   return L;
 }
@@ -143,7 +148,24 @@ ct_status ct_linear(const void* x, int32_t n_tokens, int32_t k_len, const void* 
   if (st != CT_OK) return st;
   if (n_tokens == 0) return CT_OK;
   if (!x || !w || !out) return fail(CT_ERR_NULL, "x, w and out must be non-NULL");
-  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, static_cast<hipStream_t>(stream));
+  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, nullptr, 0, 256, static_cast<hipStream_t>(stream));
+}
+
+size_t ct_linear_workspace_bytes(int32_t n_tokens, int32_t k_len, int32_t n_out) {
+  if (n_tokens <= 0 || k_len <= 0 || n_out <= 0) return 0;
+  return linear_workspace_bytes(n_tokens, k_len, n_out);
+}
+
+ct_status ct_linear_ws(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out, const void* residual,
+                       void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  ct_status st = check_gemm_shape(n_tokens, k_len, n_out);
+  if (st != CT_OK) return st;
+  if (n_tokens == 0) return CT_OK;
+  if (!x || !w || !out) return fail(CT_ERR_NULL, "x, w and out must be non-NULL");
+  if (workspace != nullptr && ((uintptr_t)workspace & 15) != 0)
+    return fail(CT_ERR_WORKSPACE, "workspace is not 16-byte aligned");
+  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, 256,
+                       static_cast<hipStream_t>(stream));
 }
 
 ct_status ct_swiglu(const void* x, int32_t n_tokens, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
@@ -342,11 +364,20 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     if ((st = launch_attention(cfg, ws + L.q, kb, vb, n_ctx, sel_idx, n_sel, ws + L.attn_out, nullptr, ws + L.attn_ws, cs)) != CT_OK)
       return st;
     if ((e = hipEventRecord(attn_done(l), cs)) != hipSuccess) return hip_fail(e, "hipEventRecord (attention done)");
-    // output projection + residual, FFN + residual (the residual stream is updated in place)
-    if ((st = launch_linear(ws + L.attn_out, n_sel, qd, lw.wo, cfg->hidden, hidden_sel, hidden_sel, cs)) != CT_OK) return st;
+    // output projection + residual, FFN + residual (the residual stream is updated in place).
+    // The chunks of layer l + 2 start streaming in when this layer's attention is done, so that
+    // kernel runs beside these GEMMs and its workgroups hold compute units of their own: the GEMM
+    // rounds are planned for what is left.  A launch's workgroups go to the eight XCDs in turn, so
+    // what counts is the XCD with the fewest free units, and the stream-in workgroups do not
+    // spread one per XCD: with 8 of them, launches planned for 216-224 units (28 per XCD) finish
+    // in one round, launches planned for 232 or more do not (measured on the config-5 stack).
+    const int gemm_cus = (l + 2 < n_layers && (streamed[0] || streamed[1])) ? 256 - 4 * stream_in_blocks() : 256;
+    if ((st = launch_linear(ws + L.attn_out, n_sel, qd, lw.wo, cfg->hidden, hidden_sel, hidden_sel, ws + L.gemm_ws,
+                            L.gemm_ws_bytes, gemm_cus, cs)) != CT_OK) return st;
     if ((st = launch_rmsnorm(hidden_sel, lw.ffn_norm, rms_eps, n_sel, cfg->hidden, ws + L.x_norm, cs)) != CT_OK) return st;
     if ((st = launch_swiglu(ws + L.x_norm, n_sel, cfg->hidden, lw.w_gate, lw.w_up, ffn_dim, ws + L.act, cs)) != CT_OK) return st;
-    if ((st = launch_linear(ws + L.act, n_sel, ffn_dim, lw.w_down, cfg->hidden, hidden_sel, hidden_sel, cs)) != CT_OK) return st;
+    if ((st = launch_linear(ws + L.act, n_sel, ffn_dim, lw.w_down, cfg->hidden, hidden_sel, hidden_sel, ws + L.gemm_ws,
+                            L.gemm_ws_bytes, gemm_cus, cs)) != CT_OK) return st;
   }
   return CT_OK;
 }

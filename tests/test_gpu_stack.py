@@ -58,6 +58,45 @@ def test_linear_with_residual(n, k_len, n_out, res):
         assert torch.equal(rt, out)
 
 
+@pytest.mark.parametrize("n,k_len,n_out,res", [(300, 8192, 4096, True),      # 32 tiles: one round, each tile split 8 ways
+                                                (4352, 2048, 4096, True),     # 272 tiles: 256 whole + 16 split 4 ways
+                                                (4915, 14336, 4096, True),    # the FFN down projection of config 5: 256 + 64 x 4
+                                                (4915, 4096, 4096, False),    # its output projection: splitting does not pay
+                                                (257, 512, 512, True)])       # too small to split: same path as ct_linear
+def test_linear_with_workspace_splits_the_last_round(n, k_len, n_out, res):
+    rng = np.random.default_rng([34, n, k_len, n_out])
+    x, w = _bits(rng, (n, k_len)), _bits(rng, (n_out, k_len), 1.0 / math.sqrt(k_len))
+    r = _bits(rng, (n, n_out)) if res else None
+    ws_bytes = B.ct_linear_workspace_bytes(n, k_len, n_out)
+    say(f"linear with workspace n={n} k={k_len} out={n_out} residual={res} workspace={ws_bytes >> 20} MiB")
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    out = torch.zeros((n, n_out), dtype=torch.bfloat16, device="cuda")
+    B.ct_linear_ws(xd, n, k_len, wd, n_out, None if r is None else dev_bf16(r), out, ws, ws_bytes)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(min(n, 64)), np.arange(max(0, n - 300), n), rng.integers(0, n, 256)]))
+    want = W.bf16_bits_to_f64(x[rows]) @ W.bf16_bits_to_f64(w).T
+    if res:
+        want = want + W.bf16_bits_to_f64(r[rows])
+    assert_close(f64_of(out)[rows], want, "linear (split reduction)")
+    # against the unsplit kernel: same values up to the order of the fp32 sums (one bf16 step at most)
+    plain = torch.zeros_like(out)
+    B.ct_linear(xd, n, k_len, wd, n_out, None if r is None else dev_bf16(r), plain)
+    torch.cuda.synchronize()
+    d = (out.float() - plain.float()).abs()
+    assert float((d / plain.float().abs().clamp_min(0.25)).max()) <= 2.0 ** -7
+    if res:   # in place on the residual
+        rt = dev_bf16(r)
+        B.ct_linear_ws(xd, n, k_len, wd, n_out, rt, rt, ws, ws_bytes)
+        torch.cuda.synchronize()
+        assert torch.equal(rt, out)
+    # too little workspace: falls back to the unsplit launch, bit-identical to ct_linear
+    small = torch.zeros_like(out)
+    B.ct_linear_ws(xd, n, k_len, wd, n_out, None if r is None else dev_bf16(r), small, ws, 1024)
+    torch.cuda.synchronize()
+    assert torch.equal(small, plain)
+
+
 @pytest.mark.parametrize("n,k_len,n_out", [(257, 512, 1408), (129, 4096, 14336), (7, 64, 64)])
 def test_swiglu(n, k_len, n_out):
     rng = np.random.default_rng([33, n, k_len, n_out])
