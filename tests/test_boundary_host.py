@@ -160,6 +160,14 @@ def test_norm_and_gemm_validation():
     assert _status(B.ct_linear, FAKE, 4, 512, FAKE, 100, None, FAKE) == B.CT_ERR_UNSUPPORTED
     assert _status(B.ct_linear, FAKE, 4, 0, FAKE, 512, None, FAKE) == B.CT_ERR_SHAPE
     assert _status(B.ct_linear, FAKE, 1 << 20, 4096, FAKE, 4096, None, FAKE) == B.CT_ERR_UNSUPPORTED   # > 4 GiB
+    assert _status(B.ct_linear_ws, FAKE, 4, 512, None, 512, None, FAKE, FAKE, 1 << 20) == B.CT_ERR_NULL
+    assert _status(B.ct_linear_ws, FAKE, 4, 500, FAKE, 512, None, FAKE, FAKE, 1 << 20) == B.CT_ERR_UNSUPPORTED
+    assert _status(B.ct_linear_ws, FAKE, 4, 512, FAKE, 512, None, FAKE, FAKE + 4, 1 << 20) == B.CT_ERR_WORKSPACE
+    B.ct_linear_ws(None, 0, 512, None, 512, None, None, None, 0)
+    # scratch: one fp32 tile per compute unit when the tiles leave a partial round, none for bad sizes
+    assert B.ct_linear_workspace_bytes(4915, 14336, 4096) == 256 * 256 * 256 * 4
+    assert B.ct_linear_workspace_bytes(100, 4096, 512) == 2 * 8 * 256 * 256 * 4
+    assert B.ct_linear_workspace_bytes(0, 4096, 512) == 0 and B.ct_linear_workspace_bytes(16, -1, 512) == 0
     assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, None, 512, FAKE) == B.CT_ERR_NULL
     assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, FAKE, 96, FAKE) == B.CT_ERR_UNSUPPORTED
     # empty work is legal and needs no GPU
