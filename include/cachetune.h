@@ -138,16 +138,21 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
 
 /* One fusion-layer step of the online pipeline (Sec. 4.2; its cost model is Eq. 9):
  *   compute stream: selective recompute of q/k/v for the selected rows
- *   copy stream   : chunks in pinned host memory (the "Transfer stream"): one kernel reads
+ *   copy stream   : chunks in pinned host memory (the "Transfer stream"): a kernel reads
  *                   them over the host link, rotates the keys on the way (Eq. 8 overlapped with
  *                   the transfer) and writes K and V to their rows of k_buf / v_buf; rows
- *                   listed in sel_idx are not transferred.  Host memory the device cannot
+ *                   listed in sel_idx are not transferred.  The chunks go in up to eight
+ *                   groups (one launch and one event each).  Host memory the device cannot
  *                   address is copied instead (one event per chunk) and rotated in place on
  *                   the compute stream
  *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
  *                   the buffers; a device chunk whose k already points at its rows of k_buf
- *                   is rotated in place and its v is left alone; then wait for the transfer
- *   compute stream: scatter, then selected-row attention.
+ *                   is rotated in place and its v is left alone
+ *   compute stream: scatter; then, per group of host chunks, wait for the group and compute
+ *                   the attention of the selected rows whose visible keys it completes (the
+ *                   chunk-wise overlap of transfer and recomputation of Sec. 4.2); with no
+ *                   host chunks, or a context so short that the key range is split over
+ *                   workgroups, one wait and one attention launch.
  * Chunks must tile buffer rows [0, n_ctx) in order (n_ctx = sum of n_tokens) with ascending
  * new positions, so that "key position <= query position" is "key row <= query row".
  *   hidden / hidden_rows / wqkv / bias as in ct_qkv_selected; the RoPE position of selected
@@ -157,7 +162,7 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
  *                a negative value disables the check
  *   attn_out     device bf16 [n_sel, n_q_heads, head_dim]
  *   workspace    at least ct_workspace_bytes(cfg, n_ctx, n_sel) bytes
- *   copy_stream  used only when a chunk has location 1; must differ from compute_stream
+ *   copy_stream  used only when a chunk has location 1 or 2; must differ from compute_stream
  *                for the copy to overlap.
  * On return (stream ordered) k_buf / v_buf hold the fused layer KV.  n_sel = 0 is the Full
  * KV Reuse case: the buffers are assembled and no attention output is produced. */

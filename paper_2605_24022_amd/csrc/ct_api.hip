@@ -191,9 +191,17 @@ int stream_in_blocks() {
   return v;
 }
 
+bool stream_in_skips_selected() {
+  static const bool v = []() {
+    const char* e = getenv("CT_STREAM_IN_SKIP_SELECTED");
+    return e == nullptr || atoi(e) != 0;
+  }();
+  return v;
+}
+
 ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
                                 void* k_buf, void* v_buf, const int32_t* sel_idx, int32_t n_sel, hipStream_t xs,
-                                bool* done) {
+                                bool* done, int group_chunks, stream_in_group_fn after_group, void* ctx) {
   *done = false;
   static const bool enabled = []() {
     const char* e = getenv("CT_STREAM_IN");
@@ -214,10 +222,8 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
   }
   ReropeChunks rc;
   memset(&rc, 0, sizeof(rc));
-  static const bool skip_selected = []() {
-    const char* e = getenv("CT_STREAM_IN_SKIP_SELECTED");
-    return e == nullptr || atoi(e) != 0;
-  }();
+  const bool skip_selected = stream_in_skips_selected();
+  int last_chunk = -1;
   auto flush = [&]() -> ct_status {
     if (rc.n == 0) return CT_OK;
     rc.tok_start[rc.n] = rc.total_tokens;
@@ -227,8 +233,10 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
     rc.n = 0;
     rc.total_tokens = 0;
     rc.compact_mask = 0;
+    if (r == CT_OK && after_group != nullptr) r = after_group(ctx, last_chunk);
     return r;
   };
+  const int per_launch = group_chunks > 0 && group_chunks < 32 ? group_chunks : 32;
   for (int c = 0; c < n_chunks; ++c) {
     const ct_chunk& ch = chunks[c];
     if (ch.location == 0) continue;
@@ -241,7 +249,8 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
     rc.row_start[i] = tab.row_start[c];
     rc.delta0[i] = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
     rc.delta_step[i] = ch.raw_keys ? 1 : 0;
-    if (rc.n == 32) {
+    last_chunk = c;
+    if (rc.n == per_launch) {
       ct_status st = flush();
       if (st != CT_OK) return st;
     }
@@ -491,7 +500,30 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   // Transfer stream: enqueue every pinned-host chunk's copy first so the DMA engine starts
   // at once; one event per chunk lets the compute stream rotate chunk c as soon as it lands.
   std::vector<hipEvent_t> landed;
-  bool streamed = false;
+  // one event per launch of the stream-in kernel, and the last chunk that launch brought in
+  struct GroupEvents {
+    hipStream_t xs;
+    std::vector<hipEvent_t> ev;
+    std::vector<int> last_chunk;
+    static ct_status record(void* self, int last) {
+      GroupEvents* g = static_cast<GroupEvents*>(self);
+      hipEvent_t ev = nullptr;
+      hipError_t err = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+      if (err == hipSuccess) err = hipEventRecord(ev, g->xs);
+      if (err != hipSuccess) {
+        if (ev) (void)hipEventDestroy(ev);
+        return hip_fail(err, "event after a stream-in launch");
+      }
+      g->ev.push_back(ev);
+      g->last_chunk.push_back(last);
+      return CT_OK;
+    }
+    void drop() {
+      for (hipEvent_t x : ev) (void)hipEventDestroy(x);   // destroying a recorded event is deferred by the runtime
+      ev.clear();
+    }
+  } groups;
+  bool streamed = false, pipelined = false;
   hipError_t e;
   if (any_host) {
     // the copies write k_buf / v_buf: they must not overtake earlier work of the compute
@@ -505,17 +537,22 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     // Preferred: a kernel on the transfer stream reads the pinned chunks over the host link,
     // rotates the keys on the way and writes keys and values to their buffer rows (Eq. 8 overlapped
     // with the transfer); one event says that all of them are in place.
-    if ((st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, sel_idx, n_sel, xs, &streamed)) != CT_OK) return st;
+    // The chunks go in groups, one launch and one event each, so that the attention of the
+    // selected rows that see only the first groups can start while the later ones are still on
+    // the link (the chunk-wise overlap of transfer and recomputation of Sec. 4.2).
+    int host_chunks = 0;
+    for (int c = 0; c < n_chunks; ++c) host_chunks += chunks[c].location != 0;
+    pipelined = n_sel > 0 && host_chunks >= 2 && stream_in_skips_selected() &&
+                plan_attention(cfg, n_ctx, n_sel).n_splits == 1;
+    groups.xs = xs;
+    st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, sel_idx, n_sel, xs, &streamed,
+                               pipelined ? (host_chunks + 7) / 8 : 0, &GroupEvents::record, &groups);
+    if (st != CT_OK) {
+      groups.drop();
+      return st;
+    }
     if (!streamed && any_compact) return fail(CT_ERR_UNSUPPORTED, "compact pools are read by the stream-in kernel only");
     landed.resize(n_chunks, nullptr);
-    if (streamed) {
-      e = hipEventCreateWithFlags(&landed[0], hipEventDisableTiming);
-      if (e == hipSuccess) e = hipEventRecord(landed[0], xs);
-      if (e != hipSuccess) {
-        if (landed[0]) (void)hipEventDestroy(landed[0]);
-        return hip_fail(e, "event after the stream-in kernel");
-      }
-    }
     // Otherwise (host memory the device cannot address): plain copies, one event per chunk.
     for (int c = 0; c < n_chunks && !streamed; ++c) {
       const ct_chunk& ch = chunks[c];
@@ -537,6 +574,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   auto drop_events = [&]() {
     for (hipEvent_t ev : landed)
       if (ev) (void)hipEventDestroy(ev);   // destroying a recorded event is deferred by the runtime
+    groups.drop();
   };
 
   // Recompute stream: projection of the selected rows runs while the copies are in flight.
@@ -586,7 +624,25 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   }
   // Pinned-host chunks: already rotated by the stream-in kernel, or rotated in place chunk by
   // chunk as soon as each copy has landed.
-  if (streamed && (e = hipStreamWaitEvent(cs, landed[0], 0)) != hipSuccess) {
+  if (streamed && pipelined) {
+    // The recomputed rows are not among those the stream-in kernel writes, so they can go to their
+    // slots now; then one attention launch per group of chunks, each for the selected rows whose
+    // last visible key that group completes.
+    st = launch_scatter(cfg, k_buf, v_buf, k_rows, v_rows, sel_idx, n_sel, cs);
+    int32_t seen = 0;
+    for (size_t j = 0; j < groups.ev.size() && st == CT_OK; ++j) {
+      if ((e = hipStreamWaitEvent(cs, groups.ev[j], 0)) != hipSuccess) {
+        st = hip_fail(e, "hipStreamWaitEvent (chunk group streamed in)");
+        break;
+      }
+      const int32_t upto = j + 1 == groups.ev.size() ? 0x7fffffff : tab.row_start[groups.last_chunk[j] + 1];
+      st = launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs, seen, upto);
+      seen = upto;
+    }
+    drop_events();
+    return st;
+  }
+  if (streamed && !groups.ev.empty() && (e = hipStreamWaitEvent(cs, groups.ev.back(), 0)) != hipSuccess) {
     drop_events();
     return hip_fail(e, "hipStreamWaitEvent (chunks streamed in)");
   }

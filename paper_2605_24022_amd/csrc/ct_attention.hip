@@ -45,6 +45,9 @@ struct AttnArgs {
   float* partial;     // workspace when n_splits > 1
   int32_t n_sel, n_ctx, Hq, Hkv, G, TM, tm_shift, cols;
   int32_t n_tiles, n_splits, split_keys;
+  // only tiles whose visible key count lies in (key_after, key_upto] are computed by this launch
+  // (the rest by other launches, each started when the rows it needs are in place)
+  int32_t key_after, key_upto;
   float scale_log2;   // softmax scale * log2(e)
 };
 
@@ -120,6 +123,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int tok0 = tile * a.TM;
   const int last_tok = min(tok0 + a.TM, a.n_sel) - 1;
   const int kmax = a.sel_idx[last_tok] + 1;              // keys this tile can see
+  if (kmax <= a.key_after || kmax > a.key_upto) return;  // another launch's tile (uniform for the workgroup)
   const int k_lo = split * a.split_keys;
   if (k_lo >= kmax) return;                              // empty split (uniform for the workgroup)
   const int k_hi = min(k_lo + a.split_keys, kmax);
@@ -451,7 +455,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 
 ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
                            int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
-                           void* workspace, hipStream_t s) {
+                           void* workspace, hipStream_t s, int32_t key_after, int32_t key_upto) {
   if (n_sel == 0) return CT_OK;
   const AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
   AttnArgs a;
@@ -474,6 +478,8 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
   a.n_tiles = p.n_tiles;
   a.n_splits = p.n_splits;
   a.split_keys = p.split_keys;
+  a.key_after = key_after;
+  a.key_upto = key_upto;
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
   a.scale_log2 = scale * 1.4426950408889634f;
 

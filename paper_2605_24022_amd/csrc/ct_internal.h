@@ -70,9 +70,15 @@ ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf
 struct ChunkTable;
 // Rows listed in sel_idx (the recompute set: their K/V are overwritten by the scatter) are not
 // transferred - the index-aware transfer of Sec. 4.2.
+// group_chunks > 0: one launch per that many chunks, and after each launch `after_group(ctx, c)` is
+// called with the index of the last chunk it covers (to record an event, say).
+typedef ct_status (*stream_in_group_fn)(void* ctx, int last_chunk);
 ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
                                 void* k_buf, void* v_buf, const int32_t* sel_idx, int32_t n_sel, hipStream_t xs,
-                                bool* done);
+                                bool* done, int group_chunks = 0, stream_in_group_fn after_group = nullptr,
+                                void* ctx = nullptr);
+// Whether the stream-in kernel leaves the rows of the recompute set alone (it does unless switched off).
+bool stream_in_skips_selected();
 ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
                          const int32_t* sel_idx, int32_t n_sel, hipStream_t s);
 // pos_of_row != NULL: position of selected token s is pos_of_row[s]; otherwise it is looked up
@@ -99,9 +105,11 @@ ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void*
                         void* out, hipStream_t s);
 // out[t, :] = x[t, :] / sqrt(mean(x[t, :]^2) + eps) * w;  x, out [n_tok, width] bf16, w [width] bf16
 ct_status launch_rmsnorm(const void* x, const void* w, float eps, int32_t n_tok, int32_t width, void* out, hipStream_t s);
+// key_after / key_upto: the launch computes only the tiles of selected rows whose last row r has
+// key_after < r + 1 <= key_upto (all tiles by default); the unsplit plan only.
 ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
                            int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
-                           void* workspace, hipStream_t s);
+                           void* workspace, hipStream_t s, int32_t key_after = 0, int32_t key_upto = 0x7fffffff);
 
 }  // namespace ct
 
