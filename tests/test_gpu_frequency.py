@@ -176,3 +176,55 @@ def test_bench_shape_all_layers_of_a_chunk():
             assert np.isin(np.nonzero(want_s > tau + 2 * tol)[0], g).all()
             assert not np.isin(np.nonzero(want_s < tau - 2 * tol)[0], g).any()
     print(f"[parity] bench-shape scores: worst error {worst:.2e} of the largest score (<= {SCORE_REL:g})", flush=True)
+
+
+def test_offline_selection_feeds_the_online_layer():
+    """The two halves together: per chunk, the index set comes from ct_select_frequency on that
+    chunk's cached K/V (Sec. 4.1); their union is the recompute set of a partial-prefill layer
+    (Sec. 4.2).  Compared with the oracle doing the same two steps."""
+    from tests.gpu_util import assert_close, dev_i32, f64_of
+    sp = W.spec(1)
+    sh = sp.shape
+    wl = W.make_workload(sp)
+    L, C, row = sp.chunk_len, sp.n_chunks, sh.n_kv_heads * sh.head_dim
+    kb, vb = W.make_spectral_kv(4242, L, row, C)                     # one (K, V) pair per chunk
+    wl.k_cache = kb.reshape(C * L, sh.n_kv_heads, sh.head_dim)
+    wl.v_cache = vb.reshape(C * L, sh.n_kv_heads, sh.head_dim)
+    alpha, ratio = 0.5, 0.15
+    per = B.ct_frequency_n_selected(L, ratio)
+    say(f"offline selection ({C} chunks of {L}) -> online layer")
+    k, v = dev_bf16(kb), dev_bf16(vb)
+    ws_bytes = B.ct_frequency_workspace_bytes(C, L, row)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    scores = torch.empty((C, L), dtype=torch.float32, device="cuda")
+    idx = torch.empty((C, per), dtype=torch.int32, device="cuda")
+    B.ct_select_frequency(k, v, C, L * row, L, row, alpha, ratio, idx, scores, ws, ws_bytes)
+    torch.cuda.synchronize()
+    sel = (idx.cpu().numpy() + (np.arange(C, dtype=np.int32) * L)[:, None]).reshape(-1).astype(np.int32)
+    want_sel = np.concatenate([O.select_frequency(W.bf16_bits_to_f64(kb[c]), W.bf16_bits_to_f64(vb[c]), alpha, ratio)[0] + c * L
+                               for c in range(C)])
+    assert np.all(np.diff(sel) > 0)
+    assert np.isin(want_sel, sel).mean() >= 0.95          # fp32 and fp64 scores may order near-ties differently
+    # online: the layer with this recompute set
+    cfg = B.cfg_from_shape(sh)
+    n_ctx, n_sel = sp.n_ctx, sel.size
+    entries = [dict(k=dev_bf16(wl.k_cache[c * L:(c + 1) * L]), v=dev_bf16(wl.v_cache[c * L:(c + 1) * L]), n_tokens=L,
+                    old_pos_start=int(wl.chunk_old_start[c]), new_pos_start=int(wl.chunk_new_start[c]), location=0)
+               for c in range(C)]
+    chunks = B.make_chunks(entries)
+    lws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
+    lws = torch.empty(max(lws_bytes, 256), dtype=torch.uint8, device="cuda")
+    k_buf = torch.zeros((n_ctx, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_buf = torch.zeros_like(k_buf)
+    out = torch.zeros((n_sel, sh.n_q_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    B.ct_partial_prefill_layer(cfg, chunks, C, dev_bf16(wl.hidden), dev_i32(sel), dev_i32(sel), n_sel, -1.0,
+                               dev_bf16(wl.wqkv), None, k_buf, v_buf, out, lws, lws_bytes, s1, s2)
+    torch.cuda.synchronize()
+    want, _, k_want, _ = O.partial_prefill_layer(W.bf16_bits_to_f64(wl.hidden[sel]), W.bf16_bits_to_f64(wl.wqkv), None,
+                                                 W.bf16_bits_to_f64(wl.k_cache), W.bf16_bits_to_f64(wl.v_cache),
+                                                 wl.old_pos, wl.new_pos, sel, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
+                                                 sh.rope_theta, sh.rope_style)
+    assert_close(f64_of(out), want, "attention output with the frequency-guided recompute set")
+    assert_close(f64_of(k_buf), k_want, "fused K with the frequency-guided recompute set")
