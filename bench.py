@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # (scaled by a plain-copy calibration; see profiles/partial_prefill_layer_cfg3_r15.md).
 # Counters cannot be read live, so the figure is only attached to the workload it was
 # measured on.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3-llama8b-32k-r15": (581.0 + 38.4) * 1024 * 1024}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3-llama8b-32k-r15": (581.7 + 38.4) * 1024 * 1024}
 
 
 def log(msg: str) -> None:
@@ -575,7 +575,20 @@ def main() -> int:
     rerope_bytes = 2.0 * (N - n) * Hkv * D * 2 + 8.0 * (N - n)      # rows that must be rotated: read + write
     scatter_bytes = 2.0 * 2.0 * n * Hkv * D * 2 + 4.0 * n
 
-    extra = {"n_ctx": N, "n_sel": n, "visible_keys": vis, "kernels": kern}
+    # spread of single steps: each of up to 30 further steps between its own pair of events on the
+    # launch stream (profiling events off)
+    pairs = []
+    for _ in range(min(args.steps, 30)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(compute)
+        step()
+        e1.record(compute)
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    single = sorted(a.elapsed_time(b) for a, b in pairs)
+
+    extra = {"n_ctx": N, "n_sel": n, "visible_keys": vis, "kernels": kern,
+             "step_ms_median": single[len(single) // 2], "step_ms_min": single[0]}
     roofline = None
     if "attention" in kern:
         t_attn = (kern["attention"]["ms_per_step"] + kern.get("merge", {}).get("ms_per_step", 0.0)) * 1e-3
