@@ -201,7 +201,8 @@ bool stream_in_skips_selected() {
 
 ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
                                 void* k_buf, void* v_buf, const int32_t* sel_idx, int32_t n_sel, hipStream_t xs,
-                                bool* done, int group_chunks, stream_in_group_fn after_group, void* ctx) {
+                                bool* done, const int* group_sizes, int n_groups, stream_in_group_fn after_group,
+                                void* ctx) {
   *done = false;
   static const bool enabled = []() {
     const char* e = getenv("CT_STREAM_IN");
@@ -223,9 +224,10 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
   ReropeChunks rc;
   memset(&rc, 0, sizeof(rc));
   const bool skip_selected = stream_in_skips_selected();
-  int last_chunk = -1;
+  int last_chunk = -1, group = 0;
   auto flush = [&]() -> ct_status {
     if (rc.n == 0) return CT_OK;
+    ++group;
     rc.tok_start[rc.n] = rc.total_tokens;
     rc.skip_rows = (skip_selected || rc.compact_mask != 0) && n_sel > 0 ? sel_idx : nullptr;
     rc.n_skip = n_sel;
@@ -236,7 +238,10 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
     if (r == CT_OK && after_group != nullptr) r = after_group(ctx, last_chunk);
     return r;
   };
-  const int per_launch = group_chunks > 0 && group_chunks < 32 ? group_chunks : 32;
+  auto per_launch = [&]() {   // chunks the launch being filled may hold
+    const int want = group_sizes != nullptr && group < n_groups - 1 ? group_sizes[group] : 32;
+    return want > 0 && want < 32 ? want : 32;
+  };
   for (int c = 0; c < n_chunks; ++c) {
     const ct_chunk& ch = chunks[c];
     if (ch.location == 0) continue;
@@ -250,7 +255,7 @@ ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks,
     rc.delta0[i] = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
     rc.delta_step[i] = ch.raw_keys ? 1 : 0;
     last_chunk = c;
-    if (rc.n == per_launch) {
+    if (rc.n == per_launch()) {
       ct_status st = flush();
       if (st != CT_OK) return st;
     }
@@ -545,8 +550,33 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     pipelined = n_sel > 0 && host_chunks >= 2 && stream_in_skips_selected() &&
                 plan_attention(cfg, n_ctx, n_sel).n_splits == 1;
     groups.xs = xs;
+    // Equal groups of chunks, as many as leave every attention launch some 200 workgroups (a
+    // launch computes the tiles of selected rows between two group ends, for every KV head; with
+    // fewer the chip is underfilled and the launches together take longer than the overlap
+    // gains: at config 4, 824 tile-head pairs, 4 groups give 13.2 ms, 8 groups 14.9, 2 groups
+    // 15.2, one launch after the last chunk 16.9; groups that end at equal attention work
+    // instead of equal rows are worse, 13.9 ms at best).
+    int sizes[8];
+    int n_groups = 0;
+    if (pipelined) {
+      const AttnPlan plan = plan_attention(cfg, n_ctx, n_sel);
+      int G = (int)((int64_t)plan.n_tiles * cfg->n_kv_heads / 200);
+      if (G > 8) G = 8;
+      if (G > host_chunks) G = host_chunks;
+      if (G < 2) {
+        pipelined = false;
+      } else {
+        int done_chunks = 0;
+        for (int g = 0; g < G; ++g) {
+          int upto = (host_chunks * (g + 1)) / G;
+          if (upto - done_chunks > 32) upto = done_chunks + 32;   // one launch holds 32 chunks at most
+          sizes[n_groups++] = upto - done_chunks;
+          done_chunks = upto;
+        }
+      }
+    }
     st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, sel_idx, n_sel, xs, &streamed,
-                               pipelined ? (host_chunks + 7) / 8 : 0, &GroupEvents::record, &groups);
+                               pipelined ? sizes : nullptr, n_groups, &GroupEvents::record, &groups);
     if (st != CT_OK) {
       groups.drop();
       return st;

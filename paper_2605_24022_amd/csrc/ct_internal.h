@@ -70,13 +70,14 @@ ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf
 struct ChunkTable;
 // Rows listed in sel_idx (the recompute set: their K/V are overwritten by the scatter) are not
 // transferred - the index-aware transfer of Sec. 4.2.
-// group_chunks > 0: one launch per that many chunks, and after each launch `after_group(ctx, c)` is
-// called with the index of the last chunk it covers (to record an event, say).
+// group_sizes != NULL: launch g covers the next group_sizes[g] host chunks (the last group takes
+// what is left), and after each launch `after_group(ctx, c)` is called with the index of the
+// last chunk it covers (to record an event, say).
 typedef ct_status (*stream_in_group_fn)(void* ctx, int last_chunk);
 ct_status stream_in_host_chunks(const ct_layer_cfg* cfg, const ct_chunk* chunks, int n_chunks, const ChunkTable& tab,
                                 void* k_buf, void* v_buf, const int32_t* sel_idx, int32_t n_sel, hipStream_t xs,
-                                bool* done, int group_chunks = 0, stream_in_group_fn after_group = nullptr,
-                                void* ctx = nullptr);
+                                bool* done, const int* group_sizes = nullptr, int n_groups = 0,
+                                stream_in_group_fn after_group = nullptr, void* ctx = nullptr);
 // Whether the stream-in kernel leaves the rows of the recompute set alone (it does unless switched off).
 bool stream_in_skips_selected();
 ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
