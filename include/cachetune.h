@@ -141,8 +141,9 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
  *   copy stream   : chunks in pinned host memory (the "Transfer stream"): a kernel reads
  *                   them over the host link, rotates the keys on the way (Eq. 8 overlapped with
  *                   the transfer) and writes K and V to their rows of k_buf / v_buf; rows
- *                   listed in sel_idx are not transferred.  The chunks go in up to eight
- *                   groups (one launch and one event each).  Host memory the device cannot
+ *                   listed in sel_idx are not transferred.  The chunks go in equal groups
+ *                   (one launch and one event each; as many groups, eight at most, as leave
+ *                   every attention launch about 200 workgroups).  Host memory the device cannot
  *                   address is copied instead (one event per chunk) and rotated in place on
  *                   the compute stream
  *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
