@@ -91,7 +91,7 @@ typedef struct {
  *   bias        device bf16 [(n_q_heads + 2 n_kv_heads) * head_dim] or NULL
  *   q_out       device bf16 [n_sel, n_q_heads, head_dim]
  *   k_out,v_out device bf16 [n_sel, n_kv_heads, head_dim]
- * n_sel = 0 is legal and does nothing. */
+ * hidden, wqkv and the three outputs must be 16-byte aligned.  n_sel = 0 is legal and does nothing. */
 ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows,
                           const int32_t* sel_pos, int32_t n_sel, const void* wqkv, const void* bias,
                           void* q_out, void* k_out, void* v_out, void* stream);
@@ -191,7 +191,7 @@ ct_status ct_rmsnorm(const void* x, const void* weight, float eps, int32_t n_tok
  *   x device bf16 [n_tokens, k_len]; w device bf16 [n_out, k_len] (one row per output feature);
  *   residual device bf16 [n_tokens, n_out] or NULL; out device bf16 [n_tokens, n_out], may equal
  *   residual (each element is read before it is written), may not overlap x.
- *   k_len and n_out multiples of 64. */
+ *   k_len and n_out multiples of 64; all four pointers 16-byte aligned. */
 ct_status ct_linear(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out, const void* residual,
                     void* out, void* stream);
 
@@ -207,7 +207,8 @@ ct_status ct_linear_ws(const void* x, int32_t n_tokens, int32_t k_len, const voi
 size_t ct_linear_workspace_bytes(int32_t n_tokens, int32_t k_len, int32_t n_out);
 
 /* out[t,:] = silu(x[t,:] * w_gate^T) * (x[t,:] * w_up^T) (SwiGLU), one kernel, bf16 result.
- *   w_gate, w_up device bf16 [n_out, k_len]; out device bf16 [n_tokens, n_out]. */
+ *   w_gate, w_up device bf16 [n_out, k_len]; out device bf16 [n_tokens, n_out]; pointers
+ *   16-byte aligned. */
 ct_status ct_swiglu(const void* x, int32_t n_tokens, int32_t k_len, const void* w_gate, const void* w_up, int32_t n_out,
                     void* out, void* stream);
 

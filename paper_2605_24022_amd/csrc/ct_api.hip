@@ -359,6 +359,8 @@ ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int
   if (n_sel == 0) return CT_OK;
   if (!hidden || !sel_pos || !wqkv || !q_out || !k_out || !v_out)
     return fail(CT_ERR_NULL, "hidden, sel_pos, wqkv, q_out, k_out and v_out must be non-NULL");
+  if ((((uintptr_t)hidden | (uintptr_t)wqkv | (uintptr_t)q_out | (uintptr_t)k_out | (uintptr_t)v_out) & 15) != 0)
+    return fail(CT_ERR_UNSUPPORTED, "hidden, wqkv, q_out, k_out and v_out must be 16-byte aligned");
   return launch_qkv(cfg, hidden, hidden_rows, sel_pos, nullptr, nullptr, n_sel, wqkv, bias, q_out, k_out, v_out,
                     static_cast<hipStream_t>(stream));
 }

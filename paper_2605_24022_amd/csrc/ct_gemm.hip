@@ -257,6 +257,22 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 
   // ---- epilogues ---------------------------------------------------------------------------------
   // accumulator element i of tile (m, n): row f0 + m*32 + 8*(i/4) + 4*hi + i%4, token = column l32
+  // In an accumulator tile the lanes l and l + 32 hold features 8g + 0..3 and 8g + 4..7 of one
+  // token (g = 0..3).  v_permlane32_swap between the packed results of groups 2q and 2q + 1 gives
+  // lane l all eight features of group 2q and lane l + 32 those of group 2q + 1, so a tile leaves as
+  // two 16-byte stores per lane instead of four 8-byte ones.  `p` points at the token's row at the
+  // tile's first feature.  Every lane of the wave must come here (the swap crosses the two halves
+  // of the wave); `ok` gates the store alone.
+  auto store_tile = [&](uint16_t* p, const f32x16& c, bool ok) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int g0 = 8 * q, g1 = 8 * q + 4;
+      const auto x0 = __builtin_amdgcn_permlane32_swap(pack_bf16(c[g0], c[g0 + 1]), pack_bf16(c[g1], c[g1 + 1]), false, false);
+      const auto x1 = __builtin_amdgcn_permlane32_swap(pack_bf16(c[g0 + 2], c[g0 + 3]), pack_bf16(c[g1 + 2], c[g1 + 3]), false, false);
+      const u32x4 out16 = {x0[0], x1[0], x0[1], x1[1]};
+      if (ok) *reinterpret_cast<u32x4*>(p + 16 * q + 8 * hi) = out16;
+    }
+  };
   if constexpr (EPI == EPI_PARTIAL) {
     // fp32 partial sums of this part of the reduction, token major inside the tile, 16-byte stores
     float* dst = a.partial + (size_t)item * (BT * BF);
@@ -274,10 +290,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
     return;
   } else if constexpr (EPI == EPI_LINEAR) {
     const int f0 = f_blk + wf * 128;
-    // All residual values of the wave's tile are fetched before the first result is stored: `out`
-    // may be the residual buffer itself, so the compiler cannot move these loads above stores on
-    // its own, and with four loads in flight per lane the epilogue is bound by memory latency.
-    u32x2 res[TW][4][4];
+    // Residuals arrive the same way, as 16-byte loads of the lane's eight features, and are swapped
+    // back into the accumulator layout.  All residual values of the wave's tile are fetched before
+    // the first result is stored: `out` may be the residual buffer itself, so the compiler cannot
+    // move these loads above stores on its own, and with few loads in flight per lane the epilogue
+    // is bound by memory latency.
+    u32x4 res[TW][4][2];
     if (a.residual != nullptr) {
 #pragma unroll
       for (int n = 0; n < TW; ++n) {
@@ -285,33 +303,38 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
           const int fm = min(f0 + m * 32, a.O - 32);
-          const size_t row = (size_t)t * a.O + fm + 4 * hi;
+          const size_t row = (size_t)t * a.O + fm + 8 * hi;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) res[n][m][g] = *reinterpret_cast<const u32x2*>(a.residual + row + 8 * g);
+          for (int q = 0; q < 2; ++q) res[n][m][q] = *reinterpret_cast<const u32x4*>(a.residual + row + 16 * q);
         }
       }
     }
 #pragma unroll
     for (int n = 0; n < TW; ++n) {
       const int t = t_blk + wt * 32 * TW + n * 32 + l32;
-      if (t >= a.n_sel) continue;
+      const bool t_ok = t < a.n_sel;
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
         const int fm = f0 + m * 32;
-        if (fm >= a.O) continue;
-        const size_t row = (size_t)t * a.O + fm + 4 * hi;
+        if (fm >= a.O) continue;            // uniform for the wave
+        if (a.residual != nullptr) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float v0 = acc[m][n][4 * g + 0], v1 = acc[m][n][4 * g + 1], v2 = acc[m][n][4 * g + 2], v3 = acc[m][n][4 * g + 3];
-          if (a.residual != nullptr) {
-            const u32x2 r = res[n][m][g];
-            v0 += bf16_lo(r[0]); v1 += bf16_hi(r[0]); v2 += bf16_lo(r[1]); v3 += bf16_hi(r[1]);
+          for (int q = 0; q < 2; ++q) {
+            // r[0], r[1]: features +0..3 of the lane's eight, r[2], r[3]: +4..7
+            const u32x4 r = res[n][m][q];
+            const auto d0 = __builtin_amdgcn_permlane32_swap(r[0], r[2], false, false);   // dword 0 of groups 2q, 2q + 1
+            const auto d1 = __builtin_amdgcn_permlane32_swap(r[1], r[3], false, false);   // dword 1
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const int i0 = 4 * (2 * q + e);
+              acc[m][n][i0 + 0] += bf16_lo(d0[e]);
+              acc[m][n][i0 + 1] += bf16_hi(d0[e]);
+              acc[m][n][i0 + 2] += bf16_lo(d1[e]);
+              acc[m][n][i0 + 3] += bf16_hi(d1[e]);
+            }
           }
-          u32x2 w;
-          w[0] = pack_bf16(v0, v1);
-          w[1] = pack_bf16(v2, v3);
-          *reinterpret_cast<u32x2*>(a.out + row + 8 * g) = w;
         }
+        store_tile(a.out + (size_t)(t_ok ? t : 0) * a.O + fm, acc[m][n], t_ok);
       }
     }
     return;
@@ -320,25 +343,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 #pragma unroll
     for (int n = 0; n < TW; ++n) {
       const int t = t_blk + wt * 32 * TW + n * 32 + l32;
-      if (t >= a.n_sel) continue;
+      const bool t_ok = t < a.n_sel;
 #pragma unroll
       for (int m = 0; m < 2; ++m) {          // gate tile m, up tile m + 2
         const int fm = f0 + m * 32;
-        if (fm >= a.O) continue;
-        const size_t row = (size_t)t * a.O + fm + 4 * hi;
+        if (fm >= a.O) continue;             // uniform for the wave
+        f32x16 y;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float v[4];
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const float gate = acc[m][n][4 * g + b], up = acc[m + 2][n][4 * g + b];
-            v[b] = gate / (1.0f + __builtin_amdgcn_exp2f(-gate * 1.4426950408889634f)) * up;   // silu(gate) * up
-          }
-          u32x2 w;
-          w[0] = pack_bf16(v[0], v[1]);
-          w[1] = pack_bf16(v[2], v[3]);
-          *reinterpret_cast<u32x2*>(a.out + row + 8 * g) = w;
+        for (int i = 0; i < 16; ++i) {
+          const float gate = acc[m][n][i], up = acc[m + 2][n][i];
+          y[i] = gate / (1.0f + __builtin_amdgcn_exp2f(-gate * 1.4426950408889634f)) * up;   // silu(gate) * up
         }
+        store_tile(a.out + (size_t)(t_ok ? t : 0) * a.O + fm, y, t_ok);
       }
     }
     return;
@@ -399,25 +415,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         }
       }
 
-      if (!t_ok) continue;
   #pragma unroll
       for (int m = 0; m < 4; ++m) {
         const int fm = f0 + m * 32;
-        if (fm >= a.O) continue;
+        if (fm >= a.O) continue;             // uniform for the wave
         uint16_t* dst;
         if (fm < q_end)
-          dst = a.q_out + (size_t)t * q_end + fm;
+          dst = a.q_out + (size_t)tc * q_end + fm;
         else if (fm < rope_end)
-          dst = a.k_out + (size_t)t * (a.Hkv * D) + (fm - q_end);
+          dst = a.k_out + (size_t)tc * (a.Hkv * D) + (fm - q_end);
         else
-          dst = a.v_out + (size_t)t * (a.Hkv * D) + (fm - rope_end);
-  #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 w;
-          w[0] = pack_bf16(acc[m][n][4 * g + 0], acc[m][n][4 * g + 1]);
-          w[1] = pack_bf16(acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]);
-          *reinterpret_cast<u32x2*>(dst + 8 * g + 4 * hi) = w;
-        }
+          dst = a.v_out + (size_t)tc * (a.Hkv * D) + (fm - rope_end);
+        store_tile(dst, acc[m][n], t_ok);
       }
     }
   }

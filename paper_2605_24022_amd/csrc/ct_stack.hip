@@ -148,6 +148,8 @@ ct_status ct_linear(const void* x, int32_t n_tokens, int32_t k_len, const void* 
   if (st != CT_OK) return st;
   if (n_tokens == 0) return CT_OK;
   if (!x || !w || !out) return fail(CT_ERR_NULL, "x, w and out must be non-NULL");
+  if ((((uintptr_t)x | (uintptr_t)w | (uintptr_t)out | (uintptr_t)residual) & 15) != 0)
+    return fail(CT_ERR_UNSUPPORTED, "x, w, residual and out must be 16-byte aligned");
   return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, nullptr, 0, 256, static_cast<hipStream_t>(stream));
 }
 
@@ -162,6 +164,8 @@ ct_status ct_linear_ws(const void* x, int32_t n_tokens, int32_t k_len, const voi
   if (st != CT_OK) return st;
   if (n_tokens == 0) return CT_OK;
   if (!x || !w || !out) return fail(CT_ERR_NULL, "x, w and out must be non-NULL");
+  if ((((uintptr_t)x | (uintptr_t)w | (uintptr_t)out | (uintptr_t)residual) & 15) != 0)
+    return fail(CT_ERR_UNSUPPORTED, "x, w, residual and out must be 16-byte aligned");
   if (workspace != nullptr && ((uintptr_t)workspace & 15) != 0)
     return fail(CT_ERR_WORKSPACE, "workspace is not 16-byte aligned");
   return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, 256,
@@ -174,6 +178,8 @@ ct_status ct_swiglu(const void* x, int32_t n_tokens, int32_t k_len, const void* 
   if (st != CT_OK) return st;
   if (n_tokens == 0) return CT_OK;
   if (!x || !w_gate || !w_up || !out) return fail(CT_ERR_NULL, "x, w_gate, w_up and out must be non-NULL");
+  if ((((uintptr_t)x | (uintptr_t)w_gate | (uintptr_t)w_up | (uintptr_t)out) & 15) != 0)
+    return fail(CT_ERR_UNSUPPORTED, "x, w_gate, w_up and out must be 16-byte aligned");
   return launch_swiglu(x, n_tokens, k_len, w_gate, w_up, n_out, out, static_cast<hipStream_t>(stream));
 }
 

@@ -168,6 +168,8 @@ def test_norm_and_gemm_validation():
     assert B.ct_linear_workspace_bytes(4915, 14336, 4096) == 256 * 256 * 256 * 4
     assert B.ct_linear_workspace_bytes(100, 4096, 512) == 2 * 8 * 256 * 256 * 4
     assert B.ct_linear_workspace_bytes(0, 4096, 512) == 0 and B.ct_linear_workspace_bytes(16, -1, 512) == 0
+    assert _status(B.ct_linear, FAKE + 8, 4, 512, FAKE, 512, None, FAKE) == B.CT_ERR_UNSUPPORTED       # alignment
+    assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, FAKE + 2, 512, FAKE) == B.CT_ERR_UNSUPPORTED
     assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, None, 512, FAKE) == B.CT_ERR_NULL
     assert _status(B.ct_swiglu, FAKE, 4, 512, FAKE, FAKE, 96, FAKE) == B.CT_ERR_UNSUPPORTED
     # empty work is legal and needs no GPU
