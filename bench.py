@@ -194,8 +194,8 @@ def bench_offline(args, B, W, np, torch) -> int:
     cnt_f, ms_f = B.ct_profile_read("frequency")
     cnt_t, ms_t = B.ct_profile_read("topk")
     B.ct_profile_reset()
-    us_f = ms_f / max(cnt_f, 1) * 1e3
-    us_t = ms_t / max(cnt_t, 1) * 1e3
+    us_f = ms_f / args.steps * 1e3 if cnt_f else 0.0     # both score kernels of a step
+    us_t = ms_t / args.steps * 1e3 if cnt_t else 0.0
     score_bytes = n_batch * (2 * n * row * 2 + n * 4)
     fft_flop = n_batch * 2 * (row // 2) * 2 * 5.0 * n * math.log2(n)
     cpu = None

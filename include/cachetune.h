@@ -309,7 +309,8 @@ ct_status ct_select_frequency(const void* k, const void* v, int32_t n_batch, int
 ct_status ct_validate_indices(const int32_t* host_idx, int32_t n_sel, int32_t n_ctx);
 
 /* Per-kernel timing for measurement runs.  With profiling on, every kernel launch the
- * library makes is bracketed by a pair of HIP events recorded on the launch stream.
+ * library makes carries a pair of HIP events on its own dispatch (begin and end of that kernel
+ * on the launch stream); nothing is put into the stream between kernels.
  * ct_profile_read waits for the recorded events of one kernel class, adds their elapsed
  * times and returns the number of launches and the summed milliseconds; ct_profile_reset
  * forgets what was recorded.  Classes: 0 qkv projection, 1 re-RoPE, 2 scatter,

@@ -69,29 +69,25 @@ static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static ProfClass g_prof[KC_COUNT];
 
-int prof_begin(KernelClass kc, hipStream_t s) {
-  if (!g_prof_on) return -1;
+void prof_events(KernelClass kc, hipEvent_t* start, hipEvent_t* stop) {
+  *start = nullptr;
+  *stop = nullptr;
+  if (!g_prof_on) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   ProfClass& p = g_prof[kc];
   if (p.used == p.start.size()) {
     hipEvent_t a, b;
-    if (hipEventCreate(&a) != hipSuccess) return -1;
+    if (hipEventCreate(&a) != hipSuccess) return;
     if (hipEventCreate(&b) != hipSuccess) {
       (void)hipEventDestroy(a);
-      return -1;
+      return;
     }
     p.start.push_back(a);
     p.stop.push_back(b);
   }
-  int slot = (int)p.used++;
-  (void)hipEventRecord(p.start[slot], s);
-  return slot;
-}
-
-void prof_end(KernelClass kc, int slot, hipStream_t s) {
-  if (slot < 0) return;
-  std::lock_guard<std::mutex> lk(g_prof_mu);
-  (void)hipEventRecord(g_prof[kc].stop[slot], s);
+  const size_t slot = p.used++;
+  *start = p.start[slot];
+  *stop = p.stop[slot];
 }
 
 // ------------------------------------------------------------------------------ planning
@@ -280,6 +276,8 @@ void ct_set_profiling(int32_t on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
   g_prof_on = on != 0;
 }
+
+
 
 ct_status ct_measure_mfma_rate(void* scratch, int32_t iters, void* stream, double* tflops) {
   if (scratch == nullptr || tflops == nullptr) return fail(CT_ERR_NULL, "scratch and tflops must be non-NULL");

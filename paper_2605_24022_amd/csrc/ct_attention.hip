@@ -486,23 +486,19 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
   const int D = cfg->head_dim;
   dim3 grid((unsigned)((size_t)p.n_tiles * cfg->n_kv_heads * p.n_splits));
   hipError_t e;
-  int slot = prof_begin(KC_ATTN, s);
   if (D == 128)
-    hipLaunchKernelGGL(attn_kernel<128>, grid, dim3(512), 0, s, a);
+    launch_kernel(KC_ATTN, attn_kernel<128>, grid, dim3(512), 0, s, a);
   else
-    hipLaunchKernelGGL(attn_kernel<64>, grid, dim3(512), 0, s, a);
-  prof_end(KC_ATTN, slot, s);
+    launch_kernel(KC_ATTN, attn_kernel<64>, grid, dim3(512), 0, s, a);
   e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
   if (p.n_splits > 1) {
     const int64_t threads = (int64_t)n_sel * cfg->n_q_heads * (D / 4);
     dim3 mgrid((unsigned)((threads + 255) / 256)), block(256);
-    slot = prof_begin(KC_MERGE, s);
     if (D == 128)
-      hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, block, 0, s, a);
+      launch_kernel(KC_MERGE, attn_merge_kernel<128>, mgrid, block, 0, s, a);
     else
-      hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, block, 0, s, a);
-    prof_end(KC_MERGE, slot, s);
+      launch_kernel(KC_MERGE, attn_merge_kernel<64>, mgrid, block, 0, s, a);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "attention merge kernel launch");
   }

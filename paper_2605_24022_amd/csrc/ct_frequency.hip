@@ -539,13 +539,11 @@ ct_status ct_frequency_scores(const void* k, const void* v, int32_t n_batch, int
   hipError_t ea = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (ea != hipSuccess) return hip_fail(ea, "hipFuncSetAttribute(freq_energy_kernel)");
   const int n_work = n_batch * 2 * p.groups;
-  int slot = prof_begin(KC_FREQ, s);
-  hipLaunchKernelGGL(kern, dim3(n_work), dim3(kFreqThreads), lds, s, (const uint16_t*)k, (const uint16_t*)v,
-                     batch_stride, row_elems, n_work, p, (float*)workspace);
+  launch_kernel(KC_FREQ, kern, dim3(n_work), dim3(kFreqThreads), (unsigned)lds, s, (const uint16_t*)k, (const uint16_t*)v,
+                batch_stride, row_elems, n_work, p, (float*)workspace);
   const int64_t total = (int64_t)n_batch * n_tokens;
-  hipLaunchKernelGGL(freq_finish_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float*)workspace,
-                     n_tokens, p.groups, n_batch, scores);
-  prof_end(KC_FREQ, slot, s);
+  launch_kernel(KC_FREQ, freq_finish_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                (const float*)workspace, n_tokens, p.groups, n_batch, scores);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "frequency score launch");
   return CT_OK;
@@ -558,9 +556,7 @@ ct_status ct_topk_indices(const float* scores, int32_t n_batch, int32_t n_tokens
   if (n_batch == 0 || k == 0) return CT_OK;
   if (scores == nullptr || idx_out == nullptr) return fail(CT_ERR_NULL, "scores and idx_out must be non-NULL");
   hipStream_t s = (hipStream_t)stream;
-  int slot = prof_begin(KC_TOPK, s);
-  hipLaunchKernelGGL(topk_kernel, dim3(n_batch), dim3(1024), 0, s, scores, n_tokens, k, idx_out);
-  prof_end(KC_TOPK, slot, s);
+  launch_kernel(KC_TOPK, topk_kernel, dim3(n_batch), dim3(1024), 0, s, scores, n_tokens, k, idx_out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "topk launch");
   return CT_OK;

@@ -489,9 +489,7 @@ static ct_status launch_gemm(Kernel kernel, int threads, const GemmArgs& a, cons
   const int items = a.v_count * a.k_parts;
   const int per_xcd = (items + 7) / 8;
   dim3 grid(per_xcd * 8), block(threads);
-  int slot = prof_begin(kc, s);
-  hipLaunchKernelGGL(kernel, grid, block, 0, s, a, rope, tab);
-  prof_end(kc, slot, s);
+  launch_kernel(kc, kernel, grid, block, 0, s, a, rope, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "gemm kernel launch");
   return CT_OK;
@@ -623,9 +621,7 @@ ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void*
       a.k_parts = parts;
       a.partial = static_cast<float*>(ws);
       if ((st = launch_variant<EPI_PARTIAL, 128, 0, 2>(a, rope, tab, KC_LINEAR, s)) != CT_OK) return st;
-      int slot = prof_begin(KC_LINEAR, s);
-      hipLaunchKernelGGL(gemm_reduce_kernel, dim3(a.v_count * 64), dim3(256), 0, s, a);
-      prof_end(KC_LINEAR, slot, s);
+      launch_kernel(KC_LINEAR, gemm_reduce_kernel, dim3(a.v_count * 64), dim3(256), 0, s, a);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return hip_fail(e, "gemm reduce launch");
       return CT_OK;

@@ -235,17 +235,17 @@ void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* k
                        const RopeTable& t, const ReropeChunks* chunks, bool big_blocks) {
   if (chunks != nullptr) {
     if (big_blocks)
-      hipLaunchKernelGGL((stream_in_kernel<D, STYLE>), grid, dim3(kStreamInThreads), 0, s, kd, vd, H, t, *chunks);
+      launch_kernel(KC_REROPE, stream_in_kernel<D, STYLE>, grid, dim3(kStreamInThreads), 0, s, kd, vd, H, t, *chunks);
     else
-      hipLaunchKernelGGL((rerope_chunks_kernel<D, STYLE, HEADS>), grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
-                         *chunks);
+      launch_kernel(KC_REROPE, rerope_chunks_kernel<D, STYLE, HEADS>, grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
+                    *chunks);
   } else {
     if (ks == kd)   // in place
-      hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS, true>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
-                         np, d0, dstep, n, H, t);
+      launch_kernel(KC_REROPE, rerope_kernel<D, STYLE, HEADS, true>, grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
+                    np, d0, dstep, n, H, t);
     else
-      hipLaunchKernelGGL((rerope_kernel<D, STYLE, HEADS, false>), grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
-                         np, d0, dstep, n, H, t);
+      launch_kernel(KC_REROPE, rerope_kernel<D, STYLE, HEADS, false>, grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
+                    np, d0, dstep, n, H, t);
   }
 }
 
@@ -274,7 +274,6 @@ ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_
   int64_t blocks = (threads + per_block - 1) / per_block;
   if (big_blocks && blocks > max_blocks) blocks = max_blocks;
   dim3 grid((unsigned)blocks);
-  int slot = prof_begin(KC_REROPE, s);
   if (D == 128) {
     if (cfg->rope_style == 0)
       launch_rerope_heads<128, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
@@ -286,7 +285,6 @@ ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_
     else
       launch_rerope_heads<64, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
   }
-  prof_end(KC_REROPE, slot, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "re-RoPE kernel launch");
   return CT_OK;
@@ -315,11 +313,9 @@ ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, cons
   const int64_t total = (int64_t)n_sel * row_vec;
   int64_t blocks = (total + 1023) / 1024;
   if (blocks > 2048) blocks = 2048;
-  int slot = prof_begin(KC_SCATTER, s);
-  hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)blocks), dim3(1024), 0, s, static_cast<u32x4*>(k_buf),
-                     static_cast<u32x4*>(v_buf), static_cast<const u32x4*>(k_sel), static_cast<const u32x4*>(v_sel),
-                     sel_idx, n_sel, row_vec);
-  prof_end(KC_SCATTER, slot, s);
+  launch_kernel(KC_SCATTER, scatter_kernel, dim3((unsigned)blocks), dim3(1024), 0, s, static_cast<u32x4*>(k_buf),
+                static_cast<u32x4*>(v_buf), static_cast<const u32x4*>(k_sel), static_cast<const u32x4*>(v_sel),
+                sel_idx, n_sel, row_vec);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "scatter kernel launch");
   return CT_OK;

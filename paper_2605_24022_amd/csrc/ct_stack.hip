@@ -108,10 +108,9 @@ StackLayout stack_layout(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx
 
 ct_status launch_rmsnorm(const void* x, const void* w, float eps, int32_t n_tok, int32_t width, void* out, hipStream_t s) {
   if (n_tok == 0) return CT_OK;
-  int slot = prof_begin(KC_NORM, s);
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3((n_tok + kNormRows - 1) / kNormRows), dim3(64 * kNormRows), 0, s, static_cast<const uint16_t*>(x),
-                     static_cast<const uint16_t*>(w), static_cast<uint16_t*>(out), n_tok, width, eps);
-  prof_end(KC_NORM, slot, s);
+  launch_kernel(KC_NORM, rmsnorm_kernel, dim3((n_tok + kNormRows - 1) / kNormRows), dim3(64 * kNormRows), 0, s,
+                static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(out), n_tok, width,
+                eps);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "rmsnorm kernel launch");
   return CT_OK;
