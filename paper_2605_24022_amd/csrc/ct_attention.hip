@@ -86,12 +86,13 @@ __device__ __forceinline__ int swz_v(int r) {
 //   M(i): O^T += V^T(i-1) P^T(i-1), then S^T(i) = K(i) Q^T            (32 MFMAs)
 // and a vector-ALU part
 //   V(i): causal mask, online softmax of S^T(i) into P^T(i), rescale of O^T.
-// The loop runs in half periods separated by workgroup barriers.  Waves 0-3 (one per SIMD)
-// run M(i) in the even and V(i) in the odd half of period i; waves 4-7 run V(i-1) in the even
-// and M(i) in the odd half.  In every half period each SIMD therefore has one wave feeding
-// the matrix cores and one wave doing softmax arithmetic, and the barriers keep it that way.
-// K(i) and V(i-1) are the tiles in use during period i; K(i+2) and V(i+1) are fetched at its
-// start with direct global->LDS loads into three K and three V stages.
+// The loop runs in periods separated by one workgroup barrier.  Waves 0-3 (one per SIMD) run
+// M(i) and then V(i) in period i; waves 4-7 run V(i-1) and then M(i).  The two parts take about
+// the same time, so each SIMD has one wave feeding the matrix cores and one wave doing softmax
+// arithmetic for most of the period without a barrier between the halves (a second barrier
+// there makes every wave wait for the slowest of eight twice per period: measured 2 % slower).
+// K(i) and V(i-1) are the tiles in use during period i; K(i+2) and V(i+1) are fetched during
+// it with direct global->LDS loads into three K and three V stages.
 template <int D>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel(AttnArgs a) {
   constexpr int NWAVES = 8;
@@ -284,10 +285,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[u][i]);
     mx = max_with_lane_xor32(mx);
-    const float m_new = fmaxf(m_run, mx * a.scale_log2);
+    // The reference of the exponents follows the running maximum lazily: it moves only when the
+    // tile's maximum exceeds it by more than 2^8, so probabilities stay below 256 (bf16 keeps
+    // their relative precision, the sums are fp32) and the rescale of O^T becomes rare.  A
+    // rescale in one wave holds up the whole workgroup at the next barrier, and with the exact
+    // maximum some wave of the eight has one in most periods.
+    const float m_tile = mx * a.scale_log2;
+    const bool changed = m_tile > m_run + 8.0f;
+    const float m_new = changed ? m_tile : m_run;
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    const bool changed = m_new > m_run;
+    const float alpha = changed ? __builtin_amdgcn_exp2f(m_run - m_use) : 1.0f;
     m_run = m_new;
     float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
@@ -340,7 +347,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   // Period i uses K(i) and V(i-1); its M parts fetch K(i+2) and V(i+1) into the stages of
   // K(i-1) and V(i-2), which nobody reads any more.  The two groups run separate loops with
-  // the same number of barriers.
+  // the same number of barriers; nothing but the order of the two parts differs, and no barrier
+  // is needed between them: both groups read the same tiles for the whole period.
   // The look-ahead loads of period i (K(i+2), V(i+1)) are issued by each wave at the start of its
   // M part, right behind the first fragment reads: the wave has to wait for those anyway, so the
   // queueing of the four waves' loads at the texture addresser costs it nothing there (measured:
@@ -354,7 +362,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i <= n_kt; ++i) {
       const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
       part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES, [&]() __attribute__((always_inline)) { refill(i, st_im1, st_ip1); });
-      __syncthreads();
       if (i < n_kt) part_v(k_lo + i * BN);
       end_of_period();
       st_im1 = st_i;
@@ -364,7 +371,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i <= n_kt; ++i) {
       const int st_ip1 = st_i == 2 ? 0 : st_i + 1;
       if (i >= 1) part_v(k_lo + (i - 1) * BN);
-      __syncthreads();
       part_m(v_lds + st_im1 * TILE_BYTES, k_lds + st_i * TILE_BYTES, [&]() __attribute__((always_inline)) { refill(i, st_im1, st_ip1); });
       end_of_period();
       st_im1 = st_i;
