@@ -229,14 +229,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // One stream of NPV + NQK (fragment read, MFMA) steps.  A step needs one A fragment from LDS;
   // with one wave per SIMD in this part nothing else hides the LDS latency, so the reads run PD
   // fragments (PD * 32 MFMA cycles) ahead of their MFMAs through a ring of PD + 1 fragment
-  // registers, across the PV -> QK boundary as well.
+  // registers, across the PV -> QK boundary as well.  The first PD fragments are read before the
+  // first MFMA can issue (a wave issues in order, one LDS instruction per ~15 cycles), so the
+  // distance is no longer than the LDS latency asks for: 3 or 4 (7 costs 1.5 %, 2 costs 1 %).
   // The wave runs it at raised priority: its instruction stream is sparse and must not queue
   // behind the dense softmax stream of the other wave on the SIMD.
   // The first period has no previous tile and the last one no next tile; both still run the
   // whole stream (P^T = 0 in the first, S^T unused in the last, the stages hold loaded data).
   constexpr int NPV = 4 * MT, NQK = 2 * KS;
 #ifndef CT_ATTN_PD
-#define CT_ATTN_PD 7
+#define CT_ATTN_PD 4
 #endif
   constexpr int PD = CT_ATTN_PD;
   auto load_frag = [&](int j, const unsigned char* vb, const unsigned char* kb) __attribute__((always_inline)) -> bf16x8 {
