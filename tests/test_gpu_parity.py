@@ -135,11 +135,20 @@ def test_qkv_selected(E, Hq, Hkv, D, theta, style, n_rows, n_sel, bias):
 
 
 # ------------------------------------------------------------------------------ selected attention
-def _attention_case(Hq, Hkv, D, n_ctx, sel, seed, rows=None, want_split=None):
+def _attention_case(Hq, Hkv, D, n_ctx, sel, seed, rows=None, want_split=None, trend=0.0):
     rng = np.random.default_rng([15, seed])
     n_sel = sel.size
-    qb = W.f32_to_bf16_bits(rng.standard_normal((n_sel, Hq, D), dtype=np.float32))
-    kb = W.f32_to_bf16_bits(rng.standard_normal((n_ctx, Hkv, D), dtype=np.float32))
+    q = rng.standard_normal((n_sel, Hq, D), dtype=np.float32)
+    k = rng.standard_normal((n_ctx, Hkv, D), dtype=np.float32)
+    if trend != 0.0:
+        # scores that drift along the keys: every query gets a component along one direction u
+        # and key j the component trend * j / n_ctx along it
+        u = rng.standard_normal(D).astype(np.float32)
+        u /= np.linalg.norm(u)
+        q += 4.0 * u
+        k += (trend * np.arange(n_ctx, dtype=np.float32) / n_ctx)[:, None, None] * u
+    qb = W.f32_to_bf16_bits(q)
+    kb = W.f32_to_bf16_bits(k)
     vb = W.f32_to_bf16_bits(rng.standard_normal((n_ctx, Hkv, D), dtype=np.float32))
     cfg = B.make_cfg(Hq * D, Hq, Hkv, D, 1e4)
     ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
@@ -185,6 +194,19 @@ def test_selected_attention_clustered_rows():
     n_ctx = 4096
     sel = np.unique(np.concatenate([np.arange(0, 64), np.arange(1000, 1128), [2000, 3000, 4095]])).astype(np.int32)
     _attention_case(32, 8, 128, n_ctx, sel, 21)
+
+
+@pytest.mark.parametrize("trend", [113.0, -113.0])
+def test_selected_attention_drifting_maximum(trend):
+    """Scores that rise (or fall) by about 40 over the context, a little per key tile: the running
+    maximum moves in most tiles by much less than the step at which the kernel moves its exponent
+    reference, so probabilities above one and a lagging reference are exercised, on rows with
+    and without key-range splits."""
+    rng = np.random.default_rng([17, int(abs(trend))])
+    for n_ctx, n_sel in ((4096, 300), (8192, 200)):
+        sel = np.sort(rng.choice(n_ctx, n_sel, replace=False)).astype(np.int32)
+        sel[-1] = n_ctx - 1
+        _attention_case(32, 8, 128, n_ctx, np.unique(sel).astype(np.int32), 31, trend=trend)
 
 
 # ------------------------------------------------------------------------------ whole layer
