@@ -328,7 +328,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
   };
 
-  // ---- the half-period loop ------------------------------------------------------------------------
+  // ---- the period loop -----------------------------------------------------------------------------
   // Loads past the last tile are still issued (row index clamped) so that the number of loads
   // outstanding at the wait, and with it the wait itself, is the same in every period.
   constexpr int LPP = 2 * INSTS;                                              // loads per wave and period
