@@ -137,7 +137,14 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* One fusion-layer step of the online pipeline (Sec. 4.2; its cost model is Eq. 9):
- *   compute stream: selective recompute of q/k/v for the selected rows
+ *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
+ *                   the buffers; a device chunk whose k already points at its rows of k_buf
+ *                   is rotated in place and its v is left alone
+ *   compute stream: selective recompute of q/k/v for the selected rows; the projection writes
+ *                   the new keys and values straight to rows sel_idx[s] of k_buf / v_buf (the
+ *                   scatter fusion of Sec. 4.2 done by the GEMM's epilogue), except when host
+ *                   chunks arrive by plain copies (below): then they wait in the workspace and
+ *                   are scattered once the copies have landed
  *   copy stream   : chunks in pinned host memory (the "Transfer stream"): a kernel reads
  *                   them over the host link, rotates the keys on the way (Eq. 8 overlapped with
  *                   the transfer) and writes K and V to their rows of k_buf / v_buf; rows
@@ -146,10 +153,7 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
  *                   every attention launch about 200 workgroups).  Host memory the device cannot
  *                   address is copied instead (one event per chunk) and rotated in place on
  *                   the compute stream
- *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
- *                   the buffers; a device chunk whose k already points at its rows of k_buf
- *                   is rotated in place and its v is left alone
- *   compute stream: scatter; then, per group of host chunks, wait for the group and compute
+ *   compute stream: per group of host chunks, wait for the group and compute
  *                   the attention of the selected rows whose visible keys it completes (the
  *                   chunk-wise overlap of transfer and recomputation of Sec. 4.2); with no
  *                   host chunks, or a context so short that the key range is split over

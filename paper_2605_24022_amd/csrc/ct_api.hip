@@ -607,14 +607,13 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     groups.drop();
   };
 
-  // Recompute stream: projection of the selected rows runs while the copies are in flight.
-  if (n_sel > 0) {
-    st = launch_qkv(cfg, hidden, hidden_rows, nullptr, sel_idx, &tab, n_sel, wqkv, bias, q_rows, k_rows, v_rows, cs);
-    if (st != CT_OK) {
-      drop_events();
-      return st;
-    }
-  }
+  // The recomputed keys and values go straight from the projection's epilogue to their rows of
+  // the layer buffers (the scatter of Sec. 4.2 fused into the GEMM) when nothing else writes those
+  // rows afterwards: the launch that rotates device chunks writes every row of its chunks and is
+  // issued first; the stream-in kernel leaves the selected rows alone; plain host copies (memory
+  // the device cannot address) overwrite them at a time of their own, so then the rows wait in
+  // the workspace and a scatter launch follows the copies.
+  const bool direct = n_sel > 0 && (!any_host || (streamed && stream_in_skips_selected()));
   // Device-resident chunks: rotated (and their values copied) into place in as few launches
   // as the table size allows; they do not wait for any copy.
   {
@@ -652,13 +651,23 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
       return st;
     }
   }
+  // Recompute stream: projection of the selected rows runs while the copies are in flight.
+  if (n_sel > 0) {
+    st = direct ? launch_qkv(cfg, hidden, hidden_rows, nullptr, sel_idx, &tab, n_sel, wqkv, bias, q_rows, k_buf, v_buf, cs,
+                             sel_idx)
+                : launch_qkv(cfg, hidden, hidden_rows, nullptr, sel_idx, &tab, n_sel, wqkv, bias, q_rows, k_rows, v_rows, cs);
+    if (st != CT_OK) {
+      drop_events();
+      return st;
+    }
+  }
   // Pinned-host chunks: already rotated by the stream-in kernel, or rotated in place chunk by
   // chunk as soon as each copy has landed.
   if (streamed && pipelined) {
-    // The recomputed rows are not among those the stream-in kernel writes, so they can go to their
-    // slots now; then one attention launch per group of chunks, each for the selected rows whose
+    // The recomputed rows are not among those the stream-in kernel writes, so they are in their
+    // slots already; one attention launch per group of chunks, each for the selected rows whose
     // last visible key that group completes.
-    st = launch_scatter(cfg, k_buf, v_buf, k_rows, v_rows, sel_idx, n_sel, cs);
+    st = CT_OK;
     int32_t seen = 0;
     for (size_t j = 0; j < groups.ev.size() && st == CT_OK; ++j) {
       if ((e = hipStreamWaitEvent(cs, groups.ev[j], 0)) != hipSuccess) {
@@ -694,8 +703,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   }
   drop_events();
   if (n_sel == 0) return CT_OK;
-  st = launch_scatter(cfg, k_buf, v_buf, k_rows, v_rows, sel_idx, n_sel, cs);
-  if (st != CT_OK) return st;
+  if (!direct && (st = launch_scatter(cfg, k_buf, v_buf, k_rows, v_rows, sel_idx, n_sel, cs)) != CT_OK) return st;
   return launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs);
 }
 

@@ -60,6 +60,9 @@ struct GemmArgs {
   uint16_t* q_out;
   uint16_t* k_out;
   uint16_t* v_out;
+  // optional: row of k_out / v_out that takes the keys and values of selected row t (the layer
+  // buffers with kv_rows = sel_idx: the scatter of the recomputed rows done by the epilogue)
+  const int32_t* kv_rows;
   int32_t Hq, Hkv;
   // EPI_LINEAR / EPI_SWIGLU: out[t, f] (+ residual[t, f]), row length O
   const uint16_t* residual;
@@ -369,6 +372,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
       const bool t_ok = t < a.n_sel;
       const int tc = t_ok ? t : a.n_sel - 1;
       const int32_t pos = a.sel_pos ? a.sel_pos[tc] : position_of_row(chunks, a.sel_idx[tc]);
+      const int32_t kv_row = a.kv_rows ? a.kv_rows[tc] : tc;
 
       if (a.bias != nullptr) {
   #pragma unroll
@@ -423,9 +427,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
         if (fm < q_end)
           dst = a.q_out + (size_t)tc * q_end + fm;
         else if (fm < rope_end)
-          dst = a.k_out + (size_t)tc * (a.Hkv * D) + (fm - q_end);
+          dst = a.k_out + (size_t)kv_row * (a.Hkv * D) + (fm - q_end);
         else
-          dst = a.v_out + (size_t)tc * (a.Hkv * D) + (fm - rope_end);
+          dst = a.v_out + (size_t)kv_row * (a.Hkv * D) + (fm - rope_end);
         store_tile(dst, acc[m][n], t_ok);
       }
     }
@@ -505,12 +509,14 @@ static ct_status launch_variant(const GemmArgs& a, const RopeTable& rope, const 
 
 ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
                      const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
-                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s) {
+                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s,
+                     const int32_t* kv_rows) {
   if (n_sel == 0) return CT_OK;
   GemmArgs a;
   memset(&a, 0, sizeof(a));
   a.hidden = static_cast<const uint16_t*>(hidden);
   a.hidden_rows = hidden_rows;
+  a.kv_rows = kv_rows;
   a.sel_pos = sel_pos;
   a.sel_idx = sel_idx;
   a.wqkv = static_cast<const uint16_t*>(wqkv);

@@ -108,7 +108,9 @@ struct ChunkTable {
 };
 ct_status launch_qkv(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows, const int32_t* sel_pos,
                      const int32_t* sel_idx, const ChunkTable* chunks, int32_t n_sel, const void* wqkv,
-                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s);
+                     const void* bias, void* q_out, void* k_out, void* v_out, hipStream_t s,
+                     const int32_t* kv_rows = nullptr);   // kv_rows != NULL: keys and values of selected row t go
+                                                          // to row kv_rows[t] of k_out / v_out (the layer buffers)
 // out[t, :] = x[t, :] * w^T (+ residual[t, :]);  x [n_tok, k_len], w [n_out, k_len], bf16
 // ws (optional, linear_workspace_bytes() bytes): scratch that lets a launch whose last round of
 // workgroups would leave most compute units idle split the reduction of those tiles.  n_cu: the

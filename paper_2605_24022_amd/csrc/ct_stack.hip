@@ -325,9 +325,12 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
 
     // attention block on the selected rows
     if ((st = launch_rmsnorm(hidden_sel, lw.attn_norm, rms_eps, n_sel, cfg->hidden, ws + L.x_norm, cs)) != CT_OK) return st;
-    if ((st = launch_qkv(cfg, ws + L.x_norm, nullptr, nullptr, sel_idx, &tab, n_sel, lw.wqkv, nullptr, ws + L.q, ws + L.k,
-                         ws + L.v, cs)) != CT_OK)
-      return st;
+    // The projection's epilogue writes the recomputed keys and values straight to their rows of
+    // the layer buffers unless plain host copies, which overwrite those rows at a time of their
+    // own, bring this layer's chunks in; device chunks are rotated into place first.
+    bool host_here = false;
+    for (int c = 0; c < n_chunks && !full; ++c) host_here |= lw.chunks[c].location != 0;
+    const bool direct = full || !host_here || (streamed[l & 1] && stream_in_skips_selected());
     if (!full) {
       ReropeChunks rc;
       memset(&rc, 0, sizeof(rc));
@@ -353,6 +356,13 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
         if (rc.n == 32 && (st = flush()) != CT_OK) return st;
       }
       if ((st = flush()) != CT_OK) return st;
+    }
+    if ((st = direct ? launch_qkv(cfg, ws + L.x_norm, nullptr, nullptr, sel_idx, &tab, n_sel, lw.wqkv, nullptr, ws + L.q, kb, vb,
+                                  cs, sel_idx)
+                     : launch_qkv(cfg, ws + L.x_norm, nullptr, nullptr, sel_idx, &tab, n_sel, lw.wqkv, nullptr, ws + L.q,
+                                  ws + L.k, ws + L.v, cs)) != CT_OK)
+      return st;
+    if (!full) {
       if (streamed[l & 1] && (e = hipStreamWaitEvent(cs, landed(l, 0), 0)) != hipSuccess)
         return hip_fail(e, "hipStreamWaitEvent (chunks streamed in)");
       for (int c = 0; c < n_chunks && !streamed[l & 1]; ++c) {
@@ -365,7 +375,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
           return st;
       }
     }
-    if ((st = launch_scatter(cfg, kb, vb, ws + L.k, ws + L.v, sel_idx, n_sel, cs)) != CT_OK) return st;
+    if (!direct && (st = launch_scatter(cfg, kb, vb, ws + L.k, ws + L.v, sel_idx, n_sel, cs)) != CT_OK) return st;
     if ((st = launch_attention(cfg, ws + L.q, kb, vb, n_ctx, sel_idx, n_sel, ws + L.attn_out, nullptr, ws + L.attn_ws, cs)) != CT_OK)
       return st;
     if ((e = hipEventRecord(attn_done(l), cs)) != hipSuccess) return hip_fail(e, "hipEventRecord (attention done)");
