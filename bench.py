@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # (scaled by a plain-copy calibration; see profiles/partial_prefill_layer_cfg3_r15.md).
 # Counters cannot be read live, so the figure is only attached to the workload it was
 # measured on.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3-llama8b-32k-r15": (581.1 + 38.4) * 1024 * 1024}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3-llama8b-32k-r15": (581.8 + 38.4) * 1024 * 1024}
 
 
 def log(msg: str) -> None:
