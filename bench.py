@@ -525,6 +525,8 @@ def main() -> int:
              n_tokens=int(wl.chunk_rows[c + 1] - wl.chunk_rows[c]), old_pos_start=int(wl.chunk_old_start[c]),
              new_pos_start=int(wl.chunk_new_start[c]), location=1 if host_pool else 0) for c in range(sp.n_chunks)])
     ws_bytes = B.ct_workspace_bytes(cfg, sp.n_ctx, sp.n_sel)
+    if host_pool:   # room for the attention state: the launches follow the chunk groups key range by key range
+        ws_bytes += B.ct_attention_state_bytes(cfg, sp.n_ctx, sp.n_sel)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
     out = torch.zeros((sp.n_sel, sh.n_q_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()

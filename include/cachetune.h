@@ -149,12 +149,16 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
  *                   them over the host link, rotates the keys on the way (Eq. 8 overlapped with
  *                   the transfer) and writes K and V to their rows of k_buf / v_buf; rows
  *                   listed in sel_idx are not transferred.  The chunks go in equal groups
- *                   (one launch and one event each; as many groups, eight at most, as leave
- *                   every attention launch about 200 workgroups).  Host memory the device cannot
+ *                   (one launch and one event each; two to eight groups, as many as leave
+ *                   every attention launch about 200 workgroups, or - with the attention
+ *                   state - as balance the work left after the last group against the cost
+ *                   of a further launch).  Host memory the device cannot
  *                   address is copied instead (one event per chunk) and rotated in place on
  *                   the compute stream
  *   compute stream: per group of host chunks, wait for the group and compute
- *                   the attention of the selected rows whose visible keys it completes (the
+ *                   the attention of the selected rows whose visible keys it completes - or,
+ *                   with the extra workspace of ct_attention_state_bytes(), of all unfinished
+ *                   rows over that group's keys (the
  *                   chunk-wise overlap of transfer and recomputation of Sec. 4.2); with no
  *                   host chunks, or a context so short that the key range is split over
  *                   workgroups, one wait and one attention launch.
@@ -180,6 +184,16 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
 /* Scratch bytes ct_selected_attention / ct_partial_prefill_layer need for this problem
  * size (0 on invalid arguments). */
 size_t ct_workspace_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel);
+
+/* Optional extra workspace of ct_partial_prefill_layer for layers whose chunks come from host
+ * memory (Sec. 4.2, overlap of transfer and recomputation): with a workspace of at least
+ * ct_workspace_bytes() + ct_attention_state_bytes() bytes the attention launch that follows a
+ * group of chunks takes every unfinished tile of selected rows through that group's keys and
+ * keeps the fp32 running (O, max, sum) of the tiles that still wait for later keys there, so
+ * only the last group's keys are left when the transfer ends.  With less the launches go tile
+ * by tile: a tile is computed once all its keys have arrived.  Host function, no GPU call;
+ * 0 for an invalid configuration or n_sel = 0. */
+size_t ct_attention_state_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel);
 
 /* ---- The rest of a transformer layer on the selected rows, and the multi-layer partial prefill.
  * After the check layer every layer of the model runs on the selected tokens only (Sec. 4.2,

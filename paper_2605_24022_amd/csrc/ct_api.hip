@@ -126,6 +126,11 @@ AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
   return p;
 }
 
+size_t attention_state_bytes(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
+  const AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
+  return (size_t)p.n_tiles * cfg->n_kv_heads * 256 * (size_t)(cfg->head_dim + 2) * sizeof(float);
+}
+
 static ct_status check_indices_host(const int32_t* idx, int32_t n_sel, int32_t n_ctx) {
   for (int32_t i = 0; i < n_sel; ++i) {
     if (idx[i] < 0 || idx[i] >= n_ctx)
@@ -348,6 +353,11 @@ size_t ct_workspace_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel)
   return up(p.ws_bytes) + q + 2 * kv + 256;
 }
 
+size_t ct_attention_state_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel) {
+  if (check_cfg(cfg) != CT_OK || n_ctx <= 0 || n_sel <= 0 || n_sel > n_ctx) return 0;
+  return (attention_state_bytes(cfg, n_ctx, n_sel) + 255) & ~(size_t)255;
+}
+
 ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows,
                           const int32_t* sel_pos, int32_t n_sel, const void* wqkv, const void* bias, void* q_out,
                           void* k_out, void* v_out, void* stream) {
@@ -492,6 +502,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   // workspace layout: [attention partials][q rows][k rows][v rows]
   char* ws = static_cast<char*>(workspace);
   void *q_rows = nullptr, *k_rows = nullptr, *v_rows = nullptr;
+  float* attn_state = nullptr;
   if (n_sel > 0) {
     AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
     size_t off = up(p.ws_bytes);
@@ -500,6 +511,11 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     k_rows = ws + off;
     off += up((size_t)n_sel * row_bytes);
     v_rows = ws + off;
+    off += up((size_t)n_sel * row_bytes);
+    // room behind the staging rows for the attention state: the attention of host-pool layers can
+    // then follow the chunk groups key range by key range
+    const size_t state_bytes = attention_state_bytes(cfg, n_ctx, n_sel);
+    if (p.n_splits == 1 && workspace_bytes >= off + state_bytes) attn_state = reinterpret_cast<float*>(ws + off);
   }
 
   // Transfer stream: enqueue every pinned-host chunk's copy first so the DMA engine starts
@@ -550,7 +566,8 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     pipelined = n_sel > 0 && host_chunks >= 2 && stream_in_skips_selected() &&
                 plan_attention(cfg, n_ctx, n_sel).n_splits == 1;
     groups.xs = xs;
-    // Equal groups of chunks, as many as leave every attention launch some 200 workgroups (a
+    // Equal groups of chunks.  Without room for the attention state: as many as leave every
+    // attention launch some 200 workgroups (a
     // launch computes the tiles of selected rows between two group ends, for every KV head; with
     // fewer the chip is underfilled and the launches together take longer than the overlap
     // gains: at config 4, 824 tile-head pairs, 4 groups give 13.2 ms, 8 groups 14.9, 2 groups
@@ -561,6 +578,21 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     if (pipelined) {
       const AttnPlan plan = plan_attention(cfg, n_ctx, n_sel);
       int G = (int)((int64_t)plan.n_tiles * cfg->n_kv_heads / 200);
+      // With room for the attention state a launch takes all unfinished tiles through the keys of
+      // one group, so the launches are full whatever the number of groups, and what is left when
+      // the transfer ends is the last group's keys: 1 / G^2 of the attention work.  Every further
+      // stream-in launch costs the link about 0.1 ms (measured at config 4: 9.34 ms in 2 launches,
+      // 9.98 in 8), so G = cbrt(2 x attention time / 0.1 ms) with the attention time estimated at
+      // 1.1 PFLOP/s: 5 groups at config 4 (10.3 ms; 4 groups 10.4, 8 groups 10.5, 2 groups 12.0).
+      if (attn_state != nullptr) {
+        static const int forced = []() {                  // tuning knob: number of chunk groups
+          const char* v = getenv("CT_ATTN_GROUPS");
+          return v != nullptr ? atoi(v) : 0;
+        }();
+        const double attn_ms = 4.0 * cfg->head_dim * cfg->n_q_heads * (0.5 * (double)n_sel * n_ctx) / 1.1e12;
+        G = forced >= 2 ? forced : (int)lround(cbrt(2.0 * attn_ms / 0.1));
+        if (G < 2) G = 2;
+      }
       if (G > 8) G = 8;
       if (G > host_chunks) G = host_chunks;
       if (G < 2) {
@@ -675,7 +707,8 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
         break;
       }
       const int32_t upto = j + 1 == groups.ev.size() ? 0x7fffffff : tab.row_start[groups.last_chunk[j] + 1];
-      st = launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs, seen, upto);
+      st = launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs, seen, upto,
+                            attn_state);
       seen = upto;
     }
     drop_events();

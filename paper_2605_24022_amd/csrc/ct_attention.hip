@@ -45,9 +45,14 @@ struct AttnArgs {
   float* partial;     // workspace when n_splits > 1
   int32_t n_sel, n_ctx, Hq, Hkv, G, TM, tm_shift, cols;
   int32_t n_tiles, n_splits, split_keys;
-  // only tiles whose visible key count lies in (key_after, key_upto] are computed by this launch
-  // (the rest by other launches, each started when the rows it needs are in place)
+  // state == NULL: only tiles whose visible key count lies in (key_after, key_upto] are computed by
+  // this launch (the rest by other launches, each started when the rows it needs are in place).
+  // state != NULL: this launch takes every tile that sees keys past key_after through the keys
+  // [key_after, key_upto) and no further; a tile that needs later keys leaves its fp32
+  // (O, m, l) in `state` ([tile][kv head][256 columns][D], then m[256], l[256]) and the launch
+  // for the next key range resumes from there.
   int32_t key_after, key_upto;
+  float* state;
   float scale_log2;   // softmax scale * log2(e)
 };
 
@@ -124,10 +129,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int tok0 = tile * a.TM;
   const int last_tok = min(tok0 + a.TM, a.n_sel) - 1;
   const int kmax = a.sel_idx[last_tok] + 1;              // keys this tile can see
-  if (kmax <= a.key_after || kmax > a.key_upto) return;  // another launch's tile (uniform for the workgroup)
-  const int k_lo = split * a.split_keys;
+  const bool resumable = a.state != nullptr;
+  if (kmax <= a.key_after || (!resumable && kmax > a.key_upto)) return;  // another launch's tile (uniform for the workgroup)
+  const int k_lo = resumable ? a.key_after : split * a.split_keys;
   if (k_lo >= kmax) return;                              // empty split (uniform for the workgroup)
-  const int k_hi = min(k_lo + a.split_keys, kmax);
+  const int k_hi = resumable ? min(a.key_upto, kmax) : min(k_lo + a.split_keys, kmax);
   const int n_kt = (k_hi - k_lo + BN - 1) / BN;
 
   // ---- this lane's query column ------------------------------------------------------------------
@@ -136,7 +142,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const bool valid = tok_raw < a.n_sel;
   const int tokv = valid ? tok_raw : a.n_sel - 1;
   const int hq = g * a.G + (col >> a.tm_shift);
-  const int pos = a.sel_idx[tokv];
+  // keys from k_hi on belong to a later launch (or to nobody): the causal mask is taken against
+  // min(position, k_hi - 1), which cuts the last key tile of the range where the range ends
+  const int pos = min(a.sel_idx[tokv], k_hi - 1);
   int wmin = pos;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) wmin = min(wmin, __shfl_xor(wmin, off));
@@ -208,6 +216,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i < 16; ++i) o[m][i] = 0.f;
   float m_run = -INFINITY;
   float l_run = 0.f;   // per-lane partial row sum; lanes l and l^32 are added at the end
+  if (resumable && k_lo > 0) {   // what the launch for the previous key range left
+    const float* base = a.state + ((size_t)tile * a.Hkv + g) * (size_t)(COLS * (D + 2));
+    const float* op = base + (size_t)col * D + 4 * hi;
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 w = *reinterpret_cast<const f32x4*>(op + m * 32 + 8 * q4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[m][4 * q4 + e] = w[e];
+      }
+    m_run = base[COLS * D + col];
+    l_run = hi == 0 ? base[COLS * D + COLS + col] : 0.f;
+  }
   f32x16 s[2];         // S^T of the tile whose scores were computed last (two 32-key sub-tiles)
   bf16x8 pf[2][2];     // P^T fragments (sub-tile u, 16-key step t) of the tile whose softmax was done last
 #pragma unroll
@@ -383,7 +405,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   // ---- epilogue -------------------------------------------------------------------------------
   const float l_tot = sum_with_lane_xor32(l_run);
-  if (kmax <= a.split_keys) {   // the tile's whole key range was this item: final result
+  if (resumable ? k_hi == kmax : kmax <= a.split_keys) {   // the tile's key range ends here: final result
     if (valid) {
       const float inv = 1.0f / l_tot;
       uint16_t* op = a.out + ((size_t)tokv * a.Hq + hq) * D + 4 * hi;
@@ -402,7 +424,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   } else {
     // partial results: [item][COLS columns][D] fp32, then m[COLS], l[COLS]
     const size_t item = ((size_t)tile * a.Hkv + g) * a.n_splits + split;
-    float* base = a.partial + item * (size_t)(COLS * (D + 2));
+    float* base = (resumable ? a.state : a.partial) + item * (size_t)(COLS * (D + 2));
     float* op = base + (size_t)col * D + 4 * hi;
 #pragma unroll
     for (int m = 0; m < MT; ++m)
@@ -463,7 +485,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 
 ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
                            int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
-                           void* workspace, hipStream_t s, int32_t key_after, int32_t key_upto) {
+                           void* workspace, hipStream_t s, int32_t key_after, int32_t key_upto, float* state) {
   if (n_sel == 0) return CT_OK;
   const AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
   AttnArgs a;
@@ -488,6 +510,7 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
   a.split_keys = p.split_keys;
   a.key_after = key_after;
   a.key_upto = key_upto;
+  a.state = state;
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
   a.scale_log2 = scale * 1.4426950408889634f;
 

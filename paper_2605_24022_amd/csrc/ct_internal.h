@@ -125,11 +125,16 @@ ct_status launch_swiglu(const void* x, int32_t n_tok, int32_t k_len, const void*
                         void* out, hipStream_t s);
 // out[t, :] = x[t, :] / sqrt(mean(x[t, :]^2) + eps) * w;  x, out [n_tok, width] bf16, w [width] bf16
 ct_status launch_rmsnorm(const void* x, const void* w, float eps, int32_t n_tok, int32_t width, void* out, hipStream_t s);
-// key_after / key_upto: the launch computes only the tiles of selected rows whose last row r has
-// key_after < r + 1 <= key_upto (all tiles by default); the unsplit plan only.
+// key_after / key_upto, the unsplit plan only.  state == NULL: the launch computes only the tiles
+// of selected rows whose last row r has key_after < r + 1 <= key_upto (all tiles by default).
+// state != NULL (attention_state_bytes() bytes): the launch takes every tile that sees keys past
+// key_after through the keys [key_after, key_upto) alone; tiles that need later keys leave their
+// fp32 (O, m, l) in `state`, where the launch for the next key range picks them up.
 ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf, const void* v_buf,
                            int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
-                           void* workspace, hipStream_t s, int32_t key_after = 0, int32_t key_upto = 0x7fffffff);
+                           void* workspace, hipStream_t s, int32_t key_after = 0, int32_t key_upto = 0x7fffffff,
+                           float* state = nullptr);
+size_t attention_state_bytes(const ct_layer_cfg* cfg, int n_ctx, int n_sel);
 
 }  // namespace ct
 

@@ -148,6 +148,9 @@ def test_workspace_size_covers_staging_and_partials():
     staging = 1638 * (32 + 16) * 128 * 2
     assert B.ct_workspace_bytes(c, 32768, 1638) > staging + 26 * 8 * 2 * 256 * 128 * 4 - 1
     assert B.ct_workspace_bytes(c, 0, 0) == 0 and B.ct_workspace_bytes(c, 100, 200) == 0
+    # the optional attention state: fp32 (O, m, l) of every 256-column tile and KV head
+    assert B.ct_attention_state_bytes(c, 32768, 4915) == 77 * 8 * 256 * 130 * 4
+    assert B.ct_attention_state_bytes(c, 32768, 0) == 0 and B.ct_attention_state_bytes(c, 100, 200) == 0
 
 
 def test_norm_and_gemm_validation():

@@ -36,21 +36,26 @@ def test_layer_config3_full_recompute_equals_full_prefill():
     _check_layer(wl, out, kb, vb, rows=rows)
 
 
-def test_layer_config4_pinned_host_chunks_clustered_rows():
-    """131072-token context streamed from pinned host memory on a second stream, clustered rows."""
+@pytest.mark.parametrize("state", [False, True])
+def test_layer_config4_pinned_host_chunks_clustered_rows(state):
+    """131072-token context streamed from pinned host memory on a second stream, clustered rows;
+    attention tile by tile as the chunk groups land, or (with room for its state) key range by key
+    range."""
     wl = W.make_workload(W.spec(4))
-    out, kb, vb = _run_layer(wl, pinned=True)
+    out, kb, vb = _run_layer(wl, pinned=True, state=state)
     rows = W.sample_rows(wl.spec.n_sel, 64, seed=4)
     _check_layer(wl, out, kb, vb, rows=rows)
 
 
+@pytest.mark.parametrize("state", [False, True])
 @pytest.mark.parametrize("pool", ["pinned", "mixed", "compact"])
-def test_layer_config3_host_pools_attention_follows_the_chunk_groups(pool):
-    """Config 3 at r = 15 % with the cached K/V outside the device: 16 chunks stream in in eight
-    groups and one attention launch per group computes the rows that group completes.  Pinned pool,
-    a pool with every third chunk on the device, and a compact pool (reused rows only)."""
+def test_layer_config3_host_pools_attention_follows_the_chunk_groups(pool, state):
+    """Config 3 at r = 15 % with the cached K/V outside the device: 16 chunks stream in in
+    groups and one attention launch per group computes the rows that group completes (or, with
+    room for the attention state, takes every unfinished row through that group's keys).  Pinned
+    pool, a pool with every third chunk on the device, and a compact pool (reused rows only)."""
     wl = W.make_workload(W.spec(3, 15))
-    out, kb, vb = _run_layer(wl, pinned=pool == "pinned", mixed=pool == "mixed", compact=pool == "compact")
+    out, kb, vb = _run_layer(wl, pinned=pool == "pinned", mixed=pool == "mixed", compact=pool == "compact", state=state)
     rows = W.sample_rows(wl.spec.n_sel, 192, seed=33)
     _check_layer(wl, out, kb, vb, rows=rows)
     assert torch.isfinite(out.float()).all()        # every tile was computed by exactly one of the launches

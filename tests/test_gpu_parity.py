@@ -210,7 +210,7 @@ def test_selected_attention_drifting_maximum(trend):
 
 
 # ------------------------------------------------------------------------------ whole layer
-def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False, mixed=False):
+def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False, mixed=False, state=False):
     sp, sh = wl.spec, wl.spec.shape
     cfg = B.cfg_from_shape(sh)
     n_ctx, n_sel = sp.n_ctx, sp.n_sel
@@ -255,7 +255,9 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, co
                             location=0 if on_device else (1 if (pinned or mixed) else 0)))
     chunks = B.make_chunks(entries)
     ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    if state:      # room for the running (O, max, sum): attention follows the chunk groups key range by key range
+        ws_bytes += B.ct_attention_state_bytes(cfg, n_ctx, n_sel)
+    ws = torch.full((max(ws_bytes, 256),), 0xff, dtype=torch.uint8, device="cuda")     # NaN patterns wherever read as fp32
     out = torch.full((n_sel, sh.n_q_heads, sh.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -286,11 +288,13 @@ def _check_layer(wl, out, k_buf, v_buf, rows=None):
     assert_close(f64_of(v_buf)[wl.sel_idx], v_want[wl.sel_idx], f"{wl.spec.name} recomputed V")
 
 
-@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned", "pageable", "compact"])
+@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned", "pinned_state", "pageable", "compact", "compact_state"])
 def test_layer_config1(mode):
     wl = W.make_workload(W.spec(1))
+    state = mode.endswith("_state")      # workspace with room for the attention state
+    mode = mode.replace("_state", "")
     out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place",
-                             pageable=mode == "pageable", compact=mode == "compact")
+                             pageable=mode == "pageable", compact=mode == "compact", state=state)
     _check_layer(wl, out, kb, vb)
 
 
