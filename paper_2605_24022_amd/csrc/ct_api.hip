@@ -583,7 +583,8 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
       // the transfer ends is the last group's keys: 1 / G^2 of the attention work.  Every further
       // stream-in launch costs the link about 0.1 ms (measured at config 4: 9.34 ms in 2 launches,
       // 9.98 in 8), so G = cbrt(2 x attention time / 0.1 ms) with the attention time estimated at
-      // 1.1 PFLOP/s: 5 groups at config 4 (10.3 ms; 4 groups 10.4, 8 groups 10.5, 2 groups 12.0).
+      // 1.1 PFLOP/s: 5 groups at config 4 (equal groups: 10.3 ms; 4 groups 10.4, 8 groups 10.5, 2
+      // groups 12.0).
       if (attn_state != nullptr) {
         static const int forced = []() {                  // tuning knob: number of chunk groups
           const char* v = getenv("CT_ATTN_GROUPS");
@@ -598,9 +599,22 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
       if (G < 2) {
         pipelined = false;
       } else {
+        // With the attention state the last group is `last_share` of the others: what is left
+        // after the transfer is that group's keys alone, and the work in them goes with the
+        // square of the group's size (config 4: 10.0 ms against 10.3 with equal groups; tuning
+        // knob CT_ATTN_LAST_GROUP, in per cent).
+        static const int last_pct = []() {
+          const char* v = getenv("CT_ATTN_LAST_GROUP");
+          const int x = v != nullptr ? atoi(v) : 50;
+          return x >= 10 && x <= 100 ? x : 50;
+        }();
+        const double last_share = attn_state != nullptr ? last_pct / 100.0 : 1.0;
+        const double unit = host_chunks / (G - 1 + last_share);
         int done_chunks = 0;
         for (int g = 0; g < G; ++g) {
-          int upto = (host_chunks * (g + 1)) / G;
+          int upto = g + 1 == G ? host_chunks : (int)lround(unit * (g + 1));
+          if (upto <= done_chunks) upto = done_chunks + 1;
+          if (upto > host_chunks - (G - 1 - g)) upto = host_chunks - (G - 1 - g);   // every group holds a chunk
           if (upto - done_chunks > 32) upto = done_chunks + 32;   // one launch holds 32 chunks at most
           sizes[n_groups++] = upto - done_chunks;
           done_chunks = upto;
