@@ -455,7 +455,8 @@ def main() -> int:
     ap.add_argument("--kv-pool", choices=["pinned", "compact", "device"], default="pinned",
                     help="config 5 only: where the per-layer cached K/V live (pinned host memory is the paper's CPU pool; "
                          "compact = pinned, holding only the rows that are not recomputed)")
-    ap.add_argument("--ratio", type=int, default=15, help="recompute ratio in percent")
+    ap.add_argument("--ratio", type=int, default=None,
+                    help="recompute ratio in percent (default: 15, and 5 for config 4, as the workloads are defined)")
     ap.add_argument("--offline-select", action="store_true",
                     help="time the offline frequency-guided selection (scores + TopK) instead of the online path")
     ap.add_argument("--tune-ratio", action="store_true",
@@ -472,6 +473,8 @@ def main() -> int:
     ap.add_argument("--no-profile-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
     args = ap.parse_args()
+    if args.ratio is None:
+        args.ratio = 5 if args.config == 4 else 15
     if args.steps is None:
         args.steps = 4 if args.config == 5 else 50
     if args.gpus != 1:
