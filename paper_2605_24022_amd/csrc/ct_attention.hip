@@ -165,7 +165,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int ld_row = wave * RPI + lane / PCS;
   const int ld_pk = (lane % PCS) ^ swz_k<D>(ld_row);
   const int ld_pv = (lane % PCS) ^ swz_v<D>(ld_row);
-  // byte offsets from the tensor bases fit 32 bits (checked on the host)
+  // byte offsets from the tensor bases fit 32 bits and row numbers 24 (checked on the host)
   const uint32_t kv_row_bytes = (uint32_t)a.Hkv * D * 2;
   const uint32_t k_lane_off = ((uint32_t)g * D + ld_pk * 8) * 2;
   const uint32_t v_lane_off = ((uint32_t)g * D + ld_pv * 8) * 2;
@@ -179,10 +179,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const uint32_t k_lds_addr = (uint32_t)(uintptr_t)(lds_ptr_t)k_lds;
   const uint32_t v_lds_addr = (uint32_t)(uintptr_t)(lds_ptr_t)v_lds;
   // One wave-wide load: rows (NWAVES * idx + wave) * RPI .. of the tile that starts at key k0.
-  // Rows past the end of the context are clamped: they are masked, or belong to look-ahead
-  // tiles that are never consumed.
+  // Rows from k_hi on (the end of this item's key range) are replaced by row k_hi - 1: they are
+  // masked (their probabilities are zero), or belong to look-ahead tiles that are never consumed,
+  // but what stands in those rows may not have been written yet - a later group of chunks still on
+  // the host link - and a non-finite bit pattern there would turn 0 * v into NaN in the PV product.
   auto issue_one = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr, int idx) __attribute__((always_inline)) {
-    const int key = min(k0 + ld_row + NWAVES * RPI * idx, a.n_ctx - 1);
+    const int key = min(k0 + ld_row + NWAVES * RPI * idx, k_hi - 1);
     dma16(base, __umul24(key, kv_row_bytes) + lane_off, stage_addr + (NWAVES * idx + wave) * 1024);
   };
   auto issue_rows = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr) __attribute__((always_inline)) {
