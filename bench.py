@@ -26,11 +26,29 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# HBM bytes per attention launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command
-# (scaled by a plain-copy calibration; see profiles/partial_prefill_layer_cfg3_r15.md).
-# Counters cannot be read live, so the figure is only attached to the workload it was
-# measured on.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3-llama8b-32k-r15": (581.8 + 38.4) * 1024 * 1024}
+# HBM bytes per attention launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command (scaled
+# by a plain-copy calibration).  Counters cannot be read live, so a figure is attached to the
+# workload it was measured on AND to the attention kernel source it was measured with: it is
+# reported only while the SHA-256 of csrc/ct_attention.hip still starts with the recorded prefix
+# (a changed kernel makes it null until the counter runs are repeated and recorded here with the
+# summary under profiles/).
+MEASURED_ATTENTION_TRAFFIC = {
+    # workload: (fetch MiB scaled, write MiB, sha256 prefix of ct_attention.hip, summary file)
+}
+
+
+def attention_traffic(workload: str):
+    """(bytes per launch, provenance) for this workload and the attention source as it stands, or (None, reason)."""
+    import hashlib
+    rec = MEASURED_ATTENTION_TRAFFIC.get(workload)
+    if rec is None:
+        return None, "no counter run recorded for this workload"
+    fetch_mib, write_mib, sha, summary = rec
+    src = os.path.join(ROOT, "paper_2605_24022_amd", "csrc", "ct_attention.hip")
+    have = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    if not have.startswith(sha):
+        return None, f"recorded with another version of the attention kernel ({sha}); see {summary}"
+    return (fetch_mib + write_mib) * 1024 * 1024, f"{summary} (attention source {sha})"
 
 
 def log(msg: str) -> None:
@@ -38,9 +56,9 @@ def log(msg: str) -> None:
 
 
 def cpu_baseline(wl, sample_rows: int, O, W, np):
-    """Time the fp64 oracle (as it stands) on a bounded sample of the same layer: the
-    projection, re-RoPE and scatter in full, attention on `sample_rows` selected rows; the
-    attention time is scaled by visible-key counts to the full row set."""
+    """Time the fp64 oracle (as it stands) on the same layer: the projection, re-RoPE and scatter
+    in full; attention in full as well (sample_rows = 0: nothing extrapolated), or on
+    `sample_rows` selected rows with its time scaled by visible-key counts to the full row set."""
     from threadpoolctl import threadpool_info
     sh = wl.spec.shape
     t0 = time.perf_counter()
@@ -58,22 +76,32 @@ def cpu_baseline(wl, sample_rows: int, O, W, np):
     t0 = time.perf_counter()
     kf, vf = O.scatter_kv(k_rot, vc, k_new, v_new, wl.sel_idx)
     t_scat = time.perf_counter() - t0
-    rows = W.sample_rows(wl.spec.n_sel, sample_rows, seed=wl.spec.seed)
+    full = sample_rows <= 0 or sample_rows >= wl.spec.n_sel
+    rows = None if full else W.sample_rows(wl.spec.n_sel, sample_rows, seed=wl.spec.seed)
     t0 = time.perf_counter()
-    O.selected_attention(q, kf, vf, wl.sel_idx, rows=rows)
+    if full:   # a few hundred rows at a time: one call would hold [n_sel, n_ctx] score matrices of gigabytes
+        for lo in range(0, wl.spec.n_sel, 512):
+            O.selected_attention(q, kf, vf, wl.sel_idx, rows=np.arange(lo, min(lo + 512, wl.spec.n_sel)))
+    else:
+        O.selected_attention(q, kf, vf, wl.sel_idx, rows=rows)
     t_attn = time.perf_counter() - t0
     vis_all = float((wl.sel_idx.astype(np.int64) + 1).sum())
-    vis_smp = float((wl.sel_idx[rows].astype(np.int64) + 1).sum())
+    vis_smp = vis_all if full else float((wl.sel_idx[rows].astype(np.int64) + 1).sum())
     t_attn_full = t_attn * vis_all / vis_smp
     total = t_qkv + t_rope + t_scat + t_attn_full
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    what = (f"attention for all {wl.spec.n_sel} selected rows ({t_attn:.2f}s, nothing extrapolated)" if full else
+            f"attention on {len(rows)} of {wl.spec.n_sel} selected rows ({t_attn:.2f}s) scaled by visible keys "
+            f"x{vis_all / vis_smp:.1f} (extrapolated)")
     return {
-        "value": total * 1e3, "unit": "ms/layer", "cores": threads, "kind": "oracle",
+        "value": total * 1e3, "unit": "ms/layer", "cores": threads, "nproc": nproc, "kind": "oracle",
         "sample": (f"fp64 NumPy oracle, same workload: QKV projection, re-RoPE and scatter in full "
-                   f"({t_qkv:.2f}s + {t_rope:.2f}s + {t_scat:.2f}s), attention on {len(rows)} of "
-                   f"{wl.spec.n_sel} selected rows ({t_attn:.2f}s) scaled by visible keys x{vis_all / vis_smp:.1f} "
-                   f"(extrapolated); bf16->f64 input conversion {t_conv:.2f}s not counted"),
-        "measured_s": {"qkv": t_qkv, "rerope": t_rope, "scatter": t_scat, "attention_sample": t_attn},
+                   f"({t_qkv:.2f}s + {t_rope:.2f}s + {t_scat:.2f}s), {what}; "
+                   f"bf16->f64 input conversion {t_conv:.2f}s not counted; {threads} BLAS threads on {nproc} host cores"),
+        "extrapolated": not full,
+        "measured_s": {"qkv": t_qkv, "rerope": t_rope, "scatter": t_scat,
+                       "attention" if full else "attention_sample": t_attn},
     }
 
 
@@ -122,9 +150,23 @@ def cold_cache_bandwidth(B, cfg, wl, sp, torch, np, reps: int = 3):
     res["rerope_in_place"] = {"avg_us": t * 1e6, "gbs_credited": credited / t / 1e9, "gbs_moved": moved / t / 1e9,
                               "frac_of_hbm_peak_credited": credited / t / 1e9 / PEAK_HBM_GBS,
                               "frac_of_hbm_peak_moved": moved / t / 1e9 / PEAK_HBM_GBS}
+    # the same rotation with the recompute set left out (rows that are overwritten by the scatter are
+    # neither read nor written): what it moves is what it is credited with
+    t = timed("rerope", lambda i: B.ct_rerope_keys_skip(cfg, kb[i], kb[i], old, new, N, sel, n, st))
+    res["rerope_in_place_reused_rows_only"] = {"avg_us": t * 1e6, "gbs": credited / t / 1e9,
+                                               "frac_of_hbm_peak": credited / t / 1e9 / PEAK_HBM_GBS}
     t = timed("scatter", lambda i: B.ct_scatter_kv(cfg, kb[i], vb[i], N, ks, vs, sel, n, st))
     sb = 2.0 * 2.0 * n * row * 2 + 4.0 * n
     res["scatter"] = {"avg_us": t * 1e6, "gbs": sb / t / 1e9, "frac_of_hbm_peak": sb / t / 1e9 / PEAK_HBM_GBS}
+    if n < N:
+        # the r = 100 % point of the same context (every row scattered: 268 MB), where the launch ramp
+        # weighs less than at 40 MB; sources rotate through the K ring as well
+        all_rows = torch.arange(N, device="cuda", dtype=torch.int32)
+        t = timed("scatter", lambda i: B.ct_scatter_kv(cfg, kb[i], vb[i], N, kb[(i + ring // 2) % ring],
+                                                       kb[(i + ring // 2 + 1) % ring], all_rows, N, st))
+        sb_all = 2.0 * 2.0 * N * row * 2 + 4.0 * N
+        res["scatter_all_rows"] = {"n_rows": N, "bytes": sb_all, "avg_us": t * 1e6, "gbs": sb_all / t / 1e9,
+                                   "frac_of_hbm_peak": sb_all / t / 1e9 / PEAK_HBM_GBS}
     # ceiling: plain device copy K ring -> V ring, same bytes as the in-place rotation moves
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     vb[0].copy_(kb[0])
@@ -400,7 +442,7 @@ def bench_stack(args, B, W, np, torch) -> int:
         kc, vc = f64(pools[0][0]), f64(pools[0][1])
         sel_np = W.select_indices(sp, n_sel)
         h0 = np.random.default_rng(1005).standard_normal((n_sel, E))
-        rows = W.sample_rows(n_sel, args.cpu_sample_rows, seed=1005)
+        rows = W.sample_rows(n_sel, args.cpu_sample_rows if args.cpu_sample_rows > 0 else 96, seed=1005)
         old_pos = (np.arange(N) % sp.chunk_len).astype(np.int32)         # keys cached at chunk-local positions
         new_pos = np.arange(N, dtype=np.int32)
         t0 = time.perf_counter()
@@ -465,7 +507,9 @@ def main() -> int:
     ap.add_argument("--r-max", type=float, default=0.60)
     ap.add_argument("--eps", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=96)
+    ap.add_argument("--cpu-sample-rows", type=int, default=-1,
+                    help="selected rows the CPU oracle's attention is timed on (0 = all; default: all rows up to the "
+                         "headline point's work, 96 rows beyond it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one plain 512 MiB device copy before the timed region (reference for HBM byte counters)")
     ap.add_argument("--no-cold-cache", action="store_true",
@@ -550,21 +594,31 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    profile = not args.no_profile_events
-    B.ct_profile_reset()
-    B.ct_set_profiling(profile)
+    # the headline: K steps back to back, nothing but the library's own launches in the streams
+    B.ct_set_profiling(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    B.ct_set_profiling(False)
     ms_per_step = elapsed * 1e3 / args.steps
 
-    # per-kernel average durations from the HIP events recorded on the launch stream
+    # second pass of the same K steps for the per-kernel split: a pair of HIP events rides on every
+    # kernel dispatch (begin and end of that kernel on its launch stream)
+    profile = not args.no_profile_events
     kern = {}
+    ms_per_step_profiled = None
     if profile:
+        B.ct_profile_reset()
+        B.ct_set_profiling(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms_per_step_profiled = (time.perf_counter() - t0) * 1e3 / args.steps
+        B.ct_set_profiling(False)
         for name in B.KERNEL_CLASSES:
             n, ms = B.ct_profile_read(name)
             if n:
@@ -593,6 +647,7 @@ def main() -> int:
     single = sorted(a.elapsed_time(b) for a, b in pairs)
 
     extra = {"n_ctx": N, "n_sel": n, "visible_keys": vis, "kernels": kern,
+             "ms_per_step_with_kernel_events": ms_per_step_profiled,
              "step_ms_median": single[len(single) // 2], "step_ms_min": single[0]}
     roofline = None
     if "attention" in kern:
@@ -603,8 +658,10 @@ def main() -> int:
         roofline = {"bound": "mfma", "kernel": "selected attention (+ split merge)", "achieved": ach,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                     "measured_mfma_only_rate": ceiling, "frac_of_measured_rate": ach / ceiling,
-                    "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get(sp.name),
+                    "traffic": attention_traffic(sp.name)[0],
                     "traffic_unit": "bytes per launch (HBM fetch + write)",
+                    "traffic_source": attention_traffic(sp.name)[1],
+                    "algorithmic_bytes_per_launch": 2.0 * n * Hq * D * 2 + 2.0 * N * Hkv * D * 2,
                     "algorithmic_flops_per_launch": attn_flops}
         extra["sel_attn_tflops"] = ach
     if "qkv" in kern:
@@ -629,7 +686,10 @@ def main() -> int:
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
         from oracle import ct_oracle as O
-        cpu = cpu_baseline(wl, args.cpu_sample_rows, O, W, np)
+        # configs 1, 2 and config 3 up to r = 15 %: the whole oracle, nothing extrapolated (about 40 s at the
+        # headline point); beyond that the attention is timed on a sample of rows
+        whole = args.cpu_sample_rows == 0 or (args.cpu_sample_rows < 0 and attn_flops <= 1.4e12)
+        cpu = cpu_baseline(wl, 0 if whole else (args.cpu_sample_rows if args.cpu_sample_rows > 0 else 96), O, W, np)
 
     line = {
         "metric": f"ms/layer partial prefill @{N // 1024}K ctx, r={sp.ratio_pct}% (sel-attn TFLOP/s and re-RoPE GB/s in extra)",

@@ -11,10 +11,11 @@
  *     vectors are int32.  "device" pointers are HIP device memory of the current device,
  *     "host" pointers are ordinary process memory, "pinned host" is hipHostMalloc memory.
  *   - KV layout is token-major [tokens, n_kv_heads, head_dim] (the paper's N x H x D).
- *   - The caller owns every buffer and both streams.  The library allocates nothing and
- *     keeps no state besides a thread-local error string, the opt-in profiling events and a
- *     pool of HIP events the stack call reuses.  `stream` arguments are
- *     hipStream_t values passed as void* (NULL = the default stream).
+ *   - The caller owns every buffer and both streams.  The library allocates no device or host
+ *     buffers and keeps no state besides a thread-local error string, the opt-in profiling events
+ *     and a small per-thread pool of HIP events (created on first use, reused by every later call
+ *     of that thread) that order the two streams in the layer and stack calls.  `stream`
+ *     arguments are hipStream_t values passed as void* (NULL = the default stream).
  *   - Calls only enqueue work: no entry point synchronises the device or the host with it.
  *     Results are valid once the stream has passed the call's last kernel.
  *   - Every host-checkable condition (NULL pointers, shapes, chunk tiling, workspace size,
@@ -22,7 +23,9 @@
  *     nothing is thrown and nothing aborts.  ct_last_error() describes the last failure of
  *     the calling thread.
  *   - Supported shapes: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads with
- *     group size n_q_heads / n_kv_heads in {1, 2, 4, 8, 16}; hidden a multiple of 64.
+ *     group size n_q_heads / n_kv_heads in {1, 2, 4, 8, 16}; hidden a multiple of 64; K/V
+ *     buffers of fewer than 2^24 rows and at most 4 GiB each; weight matrices and the rows read
+ *     of activation matrices within 4 GiB of their base (CT_ERR_UNSUPPORTED otherwise).
  */
 #ifndef CACHETUNE_H
 #define CACHETUNE_H
@@ -105,6 +108,15 @@ ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int
 ct_status ct_rerope_keys(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const int32_t* old_pos,
                          const int32_t* new_pos, int32_t n_tokens, void* stream);
 
+/* ct_rerope_keys for the reused rows alone (Eq. 8 applies to reused keys; Sec. 4.2, index-aware
+ * I/O: rows of the recompute set are not moved): rows listed in skip_rows are neither read nor
+ * written - the scatter overwrites them.
+ *   skip_rows    device int32 [n_skip], strictly ascending, in [0, n_tokens); may be NULL when
+ *                n_skip = 0 (the call is then ct_rerope_keys) */
+ct_status ct_rerope_keys_skip(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const int32_t* old_pos,
+                              const int32_t* new_pos, int32_t n_tokens, const int32_t* skip_rows, int32_t n_skip,
+                              void* stream);
+
 /* Same rotation for one chunk whose positions are contiguous (Eq. 8): token t moves from
  * old_pos_start + t to new_pos_start + t, so every token shares one delta; with
  * raw_keys != 0 token t is rotated by new_pos_start + t instead.  If v_src and v_dst are
@@ -138,8 +150,9 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
 
 /* One fusion-layer step of the online pipeline (Sec. 4.2; its cost model is Eq. 9):
  *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
- *                   the buffers; a device chunk whose k already points at its rows of k_buf
- *                   is rotated in place and its v is left alone
+ *                   the buffers (all but the rows listed in sel_idx, which are recomputed); a
+ *                   device chunk whose k already points at its rows of k_buf is rotated in
+ *                   place and its v is left alone
  *   compute stream: selective recompute of q/k/v for the selected rows; the projection writes
  *                   the new keys and values straight to rows sel_idx[s] of k_buf / v_buf (the
  *                   scatter fusion of Sec. 4.2 done by the GEMM's epilogue), except when host
@@ -164,8 +177,9 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
  *                   workgroups, one wait and one attention launch.
  * Chunks must tile buffer rows [0, n_ctx) in order (n_ctx = sum of n_tokens) with ascending
  * new positions, so that "key position <= query position" is "key row <= query row".
- *   hidden / hidden_rows / wqkv / bias as in ct_qkv_selected; the RoPE position of selected
- *   token s is the new position of buffer row sel_idx[s].
+ *   hidden / hidden_rows / wqkv / bias as in ct_qkv_selected (hidden_rows, when given, are rows
+ *   of a [n_ctx, hidden] matrix); the RoPE position of selected token s is the new position of
+ *   buffer row sel_idx[s].
  *   sel_idx      device int32 [n_sel] strictly ascending
  *   recompute_ratio  r in [0,1]: n_sel must equal floor(r * n_ctx) (1 at least when r > 0);
  *                a negative value disables the check
@@ -224,6 +238,15 @@ ct_status ct_linear_ws(const void* x, int32_t n_tokens, int32_t k_len, const voi
                        const void* residual, void* out, void* workspace, size_t workspace_bytes, void* stream);
 size_t ct_linear_workspace_bytes(int32_t n_tokens, int32_t k_len, int32_t n_out);
 
+/* ct_linear_ws planned for n_compute_units of the chip's 256 compute units instead of all of
+ * them, for a launch that runs beside kernels which keep compute units to themselves (the stack
+ * call plans the GEMMs that run beside the transfer of a later layer's chunks this way: Sec. 4.2,
+ * transfer overlapped with recomputation).  Same result as ct_linear_ws up to the order of the
+ * fp32 sums.  n_compute_units in [1, 256], CT_ERR_SHAPE otherwise. */
+ct_status ct_linear_ws_cus(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out,
+                           const void* residual, void* out, void* workspace, size_t workspace_bytes,
+                           int32_t n_compute_units, void* stream);
+
 /* out[t,:] = silu(x[t,:] * w_gate^T) * (x[t,:] * w_up^T) (SwiGLU), one kernel, bf16 result.
  *   w_gate, w_up device bf16 [n_out, k_len]; out device bf16 [n_tokens, n_out]; pointers
  *   16-byte aligned. */
@@ -255,12 +278,24 @@ typedef struct {
  *              layer l computes.  On return slot (n_layers-1) % 2 holds the last layer's fused KV.
  *   n_sel == n_ctx is ordinary full prefill: no cached KV is read or copied.
  *   workspace  at least ct_stack_workspace_bytes() bytes, 256-byte aligned.
- * Events are taken from a process-wide pool: concurrent stack calls are not supported. */
+ * Events are taken from the calling thread's pool. */
 ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, float rms_eps, const ct_layer_weights* layers,
                                    int32_t n_layers, int32_t n_chunks, void* hidden_sel, const int32_t* sel_idx,
                                    int32_t n_sel, double recompute_ratio, void* k_bufs, void* v_bufs, void* workspace,
                                    size_t workspace_bytes, void* compute_stream, void* copy_stream);
 size_t ct_stack_workspace_bytes(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx, int32_t n_sel);
+
+/* ct_partial_prefill_stack that also hands out what enters every layer (Sec. 4.2: the fusion
+ * layers' inputs are the selected tokens' hidden states): layer_inputs, device bf16
+ * [n_layers, n_sel, hidden], receives the rows of hidden_sel as layer l reads them (a device copy
+ * on compute_stream per layer); layer l's output is layer l + 1's input, the last layer's is
+ * hidden_sel.  For inspecting or checking single layers of a run; NULL makes the call
+ * ct_partial_prefill_stack. */
+ct_status ct_partial_prefill_stack_tap(const ct_layer_cfg* cfg, int32_t ffn_dim, float rms_eps,
+                                       const ct_layer_weights* layers, int32_t n_layers, int32_t n_chunks,
+                                       void* hidden_sel, const int32_t* sel_idx, int32_t n_sel, double recompute_ratio,
+                                       void* k_bufs, void* v_bufs, void* workspace, size_t workspace_bytes,
+                                       void* compute_stream, void* copy_stream, void* layer_inputs);
 
 /* ---- Choice of the recomputation ratio for a given GPU and cache pool (Sec. 4.3).  Host code. ---- */
 

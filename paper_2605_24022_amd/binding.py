@@ -21,10 +21,10 @@ CT_ERR_WORKSPACE, CT_ERR_HIP, CT_ERR_UNSUPPORTED = -5, -6, -7
 KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 4, "linear": 5, "norm": 6, "frequency": 7, "topk": 8}
 
 EXPORTS = [
-    "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
+    "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_keys_skip", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
     "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_attention_state_bytes", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
-    "ct_rmsnorm", "ct_linear", "ct_linear_ws", "ct_linear_workspace_bytes", "ct_swiglu", "ct_partial_prefill_stack", "ct_stack_workspace_bytes",
+    "ct_rmsnorm", "ct_linear", "ct_linear_ws", "ct_linear_ws_cus", "ct_linear_workspace_bytes", "ct_swiglu", "ct_partial_prefill_stack", "ct_partial_prefill_stack_tap", "ct_stack_workspace_bytes",
     "ct_measure_mfma_rate", "ct_layer_latency_model", "ct_ratio_prior", "ct_ratio_search",
     "ct_frequency_scores", "ct_frequency_workspace_bytes", "ct_topk_indices", "ct_frequency_n_selected",
     "ct_select_frequency",
@@ -73,6 +73,7 @@ def load() -> ctypes.CDLL:
     cfgp = POINTER(LayerCfg)
     lib.ct_qkv_selected.argtypes = [cfgp, P, P, P, c_int32, P, P, P, P, P, P]
     lib.ct_rerope_keys.argtypes = [cfgp, P, P, P, P, c_int32, P]
+    lib.ct_rerope_keys_skip.argtypes = [cfgp, P, P, P, P, c_int32, P, c_int32, P]
     lib.ct_rerope_chunk.argtypes = [cfgp, P, P, P, P, c_int32, c_int32, c_int32, c_int32, P]
     lib.ct_scatter_kv.argtypes = [cfgp, P, P, c_int32, P, P, P, c_int32, P]
     lib.ct_selected_attention.argtypes = [cfgp, P, P, P, c_int32, P, c_int32, P, P, P, c_size_t, P]
@@ -81,11 +82,15 @@ def load() -> ctypes.CDLL:
     lib.ct_rmsnorm.argtypes = [P, P, c_float, c_int32, c_int32, P, P]
     lib.ct_linear.argtypes = [P, c_int32, c_int32, P, c_int32, P, P, P]
     lib.ct_linear_ws.argtypes = [P, c_int32, c_int32, P, c_int32, P, P, P, c_size_t, P]
+    lib.ct_linear_ws_cus.argtypes = [P, c_int32, c_int32, P, c_int32, P, P, P, c_size_t, c_int32, P]
     lib.ct_linear_workspace_bytes.argtypes = [c_int32, c_int32, c_int32]
     lib.ct_linear_workspace_bytes.restype = c_size_t
     lib.ct_swiglu.argtypes = [P, c_int32, c_int32, P, P, c_int32, P, P]
     lib.ct_partial_prefill_stack.argtypes = [cfgp, c_int32, c_float, POINTER(LayerWeights), c_int32, c_int32, P, P,
                                              c_int32, c_double, P, P, P, c_size_t, P, P]
+    lib.ct_partial_prefill_stack_tap.argtypes = [cfgp, c_int32, c_float, POINTER(LayerWeights), c_int32, c_int32, P, P,
+                                                 c_int32, c_double, P, P, P, c_size_t, P, P, P]
+    lib.ct_partial_prefill_stack_tap.restype = c_int32
     lib.ct_stack_workspace_bytes.argtypes = [cfgp, c_int32, c_int32, c_int32]
     lib.ct_stack_workspace_bytes.restype = c_size_t
     lib.ct_workspace_bytes.argtypes = [cfgp, c_int32, c_int32]
@@ -118,7 +123,7 @@ def load() -> ctypes.CDLL:
     lib.ct_measure_mfma_rate.restype = c_int32
     lib.ct_last_error.restype = c_char_p
     lib.ct_version.restype = c_char_p
-    for name in ("ct_qkv_selected", "ct_rerope_keys", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
+    for name in ("ct_qkv_selected", "ct_rerope_keys", "ct_rerope_keys_skip", "ct_linear_ws_cus", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
                  "ct_partial_prefill_layer", "ct_validate_indices", "ct_profile_read", "ct_rmsnorm", "ct_linear",
                  "ct_linear_ws", "ct_swiglu", "ct_partial_prefill_stack"):
         getattr(lib, name).restype = c_int32
@@ -190,6 +195,11 @@ def ct_rerope_keys(cfg, k_src, k_dst, old_pos, new_pos, n_tokens, stream=None) -
                                  _stream(stream)))
 
 
+def ct_rerope_keys_skip(cfg, k_src, k_dst, old_pos, new_pos, n_tokens, skip_rows, n_skip, stream=None) -> None:
+    _check(load().ct_rerope_keys_skip(byref(cfg), _ptr(k_src), _ptr(k_dst), _ptr(old_pos), _ptr(new_pos), n_tokens,
+                                      _ptr(skip_rows), n_skip, _stream(stream)))
+
+
 def ct_rerope_chunk(cfg, k_src, k_dst, v_src, v_dst, n_tokens, old_pos_start, new_pos_start, raw_keys=0,
                     stream=None) -> None:
     _check(load().ct_rerope_chunk(byref(cfg), _ptr(k_src), _ptr(k_dst), _ptr(v_src), _ptr(v_dst), n_tokens,
@@ -244,6 +254,12 @@ def ct_linear_ws(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspa
                                workspace_bytes, _stream(stream)))
 
 
+def ct_linear_ws_cus(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, n_compute_units,
+                     stream=None) -> None:
+    _check(load().ct_linear_ws_cus(_ptr(x), n_tokens, k_len, _ptr(w), n_out, _ptr(residual), _ptr(out), _ptr(workspace),
+                                   workspace_bytes, n_compute_units, _stream(stream)))
+
+
 def ct_swiglu(x, n_tokens, k_len, w_gate, w_up, n_out, out, stream=None) -> None:
     _check(load().ct_swiglu(_ptr(x), n_tokens, k_len, _ptr(w_gate), _ptr(w_up), n_out, _ptr(out), _stream(stream)))
 
@@ -273,6 +289,15 @@ def ct_partial_prefill_stack(cfg, ffn_dim, rms_eps, layers, n_layers, n_chunks, 
                                            _ptr(hidden_sel), _ptr(sel_idx), n_sel, float(recompute_ratio),
                                            _ptr(k_bufs), _ptr(v_bufs), _ptr(workspace), workspace_bytes,
                                            _stream(compute_stream), _stream(copy_stream)))
+
+
+def ct_partial_prefill_stack_tap(cfg, ffn_dim, rms_eps, layers, n_layers, n_chunks, hidden_sel, sel_idx, n_sel,
+                                 recompute_ratio, k_bufs, v_bufs, workspace, workspace_bytes, compute_stream=None,
+                                 copy_stream=None, layer_inputs=None) -> None:
+    _check(load().ct_partial_prefill_stack_tap(byref(cfg), ffn_dim, float(rms_eps), layers, n_layers, n_chunks,
+                                               _ptr(hidden_sel), _ptr(sel_idx), n_sel, float(recompute_ratio),
+                                               _ptr(k_bufs), _ptr(v_bufs), _ptr(workspace), workspace_bytes,
+                                               _stream(compute_stream), _stream(copy_stream), _ptr(layer_inputs)))
 
 
 def ct_set_profiling(on: bool) -> None:

@@ -90,6 +90,19 @@ void prof_events(KernelClass kc, hipEvent_t* start, hipEvent_t* stop) {
   *stop = p.stop[slot];
 }
 
+// ------------------------------------------------------------------------------ stream-ordering events
+ct_status pooled_events(size_t n, hipEvent_t** out) {
+  static thread_local std::vector<hipEvent_t> pool;
+  while (pool.size() < n) {
+    hipEvent_t e;
+    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    if (err != hipSuccess) return hip_fail(err, "hipEventCreate");
+    pool.push_back(e);
+  }
+  *out = pool.data();
+  return CT_OK;
+}
+
 // ------------------------------------------------------------------------------ planning
 AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
   AttnPlan p;
@@ -126,9 +139,31 @@ AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
   return p;
 }
 
+size_t attention_scratch_bytes(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
+  return plan_attention(cfg, n_ctx, n_sel).ws_bytes;
+}
+
 size_t attention_state_bytes(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
   const AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
   return (size_t)p.n_tiles * cfg->n_kv_heads * 256 * (size_t)(cfg->head_dim + 2) * sizeof(float);
+}
+
+// The attention kernel forms key-row byte offsets in 32 bits from a 24-bit row number.
+ct_status check_kv_extent(const ct_layer_cfg* cfg, int64_t n_ctx) {
+  if ((uint64_t)n_ctx * cfg->n_kv_heads * cfg->head_dim * 2 > 0xffffffffull)
+    return fail(CT_ERR_UNSUPPORTED, "K/V buffers beyond 4 GiB each (n_ctx %lld) are not supported", (long long)n_ctx);
+  if (n_ctx >= (1 << 24)) return fail(CT_ERR_UNSUPPORTED, "n_ctx %lld: at most 2^24 - 1 rows are supported", (long long)n_ctx);
+  return CT_OK;
+}
+
+// The projection kernel forms byte offsets into `hidden` and `wqkv` in 32 bits.
+static ct_status check_qkv_extent(const ct_layer_cfg* cfg, int64_t hidden_rows_spanned) {
+  const uint64_t o = (uint64_t)(cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+  if (o * cfg->hidden * 2 > 0xffffffffull) return fail(CT_ERR_UNSUPPORTED, "wqkv beyond 4 GiB is not supported");
+  if ((uint64_t)hidden_rows_spanned * cfg->hidden * 2 > 0xffffffffull)
+    return fail(CT_ERR_UNSUPPORTED, "hidden rows beyond 4 GiB from the base (%lld rows of %d) are not supported",
+                (long long)hidden_rows_spanned, cfg->hidden);
+  return CT_OK;
 }
 
 static ct_status check_indices_host(const int32_t* idx, int32_t n_sel, int32_t n_ctx) {
@@ -369,6 +404,8 @@ ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int
     return fail(CT_ERR_NULL, "hidden, sel_pos, wqkv, q_out, k_out and v_out must be non-NULL");
   if ((((uintptr_t)hidden | (uintptr_t)wqkv | (uintptr_t)q_out | (uintptr_t)k_out | (uintptr_t)v_out) & 15) != 0)
     return fail(CT_ERR_UNSUPPORTED, "hidden, wqkv, q_out, k_out and v_out must be 16-byte aligned");
+  // with a row gather the rows read are the caller's to keep within 4 GiB of the base (device data)
+  if ((st = check_qkv_extent(cfg, hidden_rows != nullptr ? 0 : n_sel)) != CT_OK) return st;
   return launch_qkv(cfg, hidden, hidden_rows, sel_pos, nullptr, nullptr, n_sel, wqkv, bias, q_out, k_out, v_out,
                     static_cast<hipStream_t>(stream));
 }
@@ -382,6 +419,20 @@ ct_status ct_rerope_keys(const ct_layer_cfg* cfg, const void* k_src, void* k_dst
   if (!k_src || !k_dst || !new_pos) return fail(CT_ERR_NULL, "k_src, k_dst and new_pos must be non-NULL");
   return launch_rerope(cfg, k_src, k_dst, nullptr, nullptr, old_pos, new_pos, 0, 0, n_tokens,
                        static_cast<hipStream_t>(stream));
+}
+
+ct_status ct_rerope_keys_skip(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const int32_t* old_pos,
+                              const int32_t* new_pos, int32_t n_tokens, const int32_t* skip_rows, int32_t n_skip,
+                              void* stream) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (n_tokens < 0 || n_skip < 0) return fail(CT_ERR_SHAPE, "negative size (n_tokens %d, n_skip %d)", n_tokens, n_skip);
+  if (n_skip > n_tokens) return fail(CT_ERR_SHAPE, "n_skip %d exceeds n_tokens %d", n_skip, n_tokens);
+  if (n_tokens == 0) return CT_OK;
+  if (!k_src || !k_dst || !new_pos) return fail(CT_ERR_NULL, "k_src, k_dst and new_pos must be non-NULL");
+  if (n_skip > 0 && !skip_rows) return fail(CT_ERR_NULL, "skip_rows is NULL but n_skip is %d", n_skip);
+  return launch_rerope(cfg, k_src, k_dst, nullptr, nullptr, old_pos, new_pos, 0, 0, n_tokens,
+                       static_cast<hipStream_t>(stream), skip_rows, n_skip);
 }
 
 ct_status ct_rerope_chunk(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src, void* v_dst,
@@ -421,8 +472,7 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
   if (n_sel == 0) return CT_OK;
   if (!q_sel || !k_buf || !v_buf || !sel_idx || !out)
     return fail(CT_ERR_NULL, "q_sel, k_buf, v_buf, sel_idx and out must be non-NULL");
-  if ((uint64_t)n_ctx * cfg->n_kv_heads * cfg->head_dim * 2 > 0xffffffffull)
-    return fail(CT_ERR_UNSUPPORTED, "K/V buffers beyond 4 GiB each (n_ctx %d) are not supported", n_ctx);
+  if ((st = check_kv_extent(cfg, n_ctx)) != CT_OK) return st;
   AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
   if (p.ws_bytes > 0) {
     if (workspace == nullptr) return fail(CT_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", p.ws_bytes);
@@ -473,8 +523,9 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   const int32_t n_ctx = (int32_t)n_ctx64;
   tab.row_start[n_chunks] = n_ctx;
   if (n_sel > n_ctx) return fail(CT_ERR_SHAPE, "n_sel %d exceeds n_ctx %d", n_sel, n_ctx);
-  if ((uint64_t)n_ctx * cfg->n_kv_heads * cfg->head_dim * 2 > 0xffffffffull)
-    return fail(CT_ERR_UNSUPPORTED, "K/V buffers beyond 4 GiB each (n_ctx %d) are not supported", n_ctx);
+  if ((st = check_kv_extent(cfg, n_ctx)) != CT_OK) return st;
+  // hidden_rows, when given, index the context's rows of `hidden`
+  if (n_sel > 0 && (st = check_qkv_extent(cfg, hidden_rows != nullptr ? n_ctx : n_sel)) != CT_OK) return st;
   if (recompute_ratio >= 0.0) {
     if (!(recompute_ratio <= 1.0)) return fail(CT_ERR_RATIO, "recompute_ratio %g is above 1", recompute_ratio);
     int64_t want = (int64_t)floor(recompute_ratio * (double)n_ctx + 1e-9);
@@ -518,30 +569,25 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     if (p.n_splits == 1 && workspace_bytes >= off + state_bytes) attn_state = reinterpret_cast<float*>(ws + off);
   }
 
-  // Transfer stream: enqueue every pinned-host chunk's copy first so the DMA engine starts
-  // at once; one event per chunk lets the compute stream rotate chunk c as soon as it lands.
-  std::vector<hipEvent_t> landed;
+  // Transfer stream: enqueue every pinned-host chunk's transfer first so the link starts at once.
+  // Events (from the per-thread pool): one fence, one per launch of the stream-in kernel (at most
+  // 8 groups), or - when the chunks have to be copied - one per chunk.
+  hipEvent_t* ev_pool = nullptr;
+  if (any_host && (st = pooled_events((size_t)1 + 8 + n_chunks, &ev_pool)) != CT_OK) return st;
+  hipEvent_t* landed = ev_pool != nullptr ? ev_pool + 9 : nullptr;   // landed[c]: chunk c has been copied
   // one event per launch of the stream-in kernel, and the last chunk that launch brought in
   struct GroupEvents {
     hipStream_t xs;
-    std::vector<hipEvent_t> ev;
-    std::vector<int> last_chunk;
+    hipEvent_t* ev;
+    int n = 0;
+    int last_chunk[8];
     static ct_status record(void* self, int last) {
       GroupEvents* g = static_cast<GroupEvents*>(self);
-      hipEvent_t ev = nullptr;
-      hipError_t err = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
-      if (err == hipSuccess) err = hipEventRecord(ev, g->xs);
-      if (err != hipSuccess) {
-        if (ev) (void)hipEventDestroy(ev);
-        return hip_fail(err, "event after a stream-in launch");
-      }
-      g->ev.push_back(ev);
-      g->last_chunk.push_back(last);
+      if (g->n >= 8) return fail(CT_ERR_HIP, "more than 8 stream-in launches in one layer");
+      hipError_t err = hipEventRecord(g->ev[g->n], g->xs);
+      if (err != hipSuccess) return hip_fail(err, "event after a stream-in launch");
+      g->last_chunk[g->n++] = last;
       return CT_OK;
-    }
-    void drop() {
-      for (hipEvent_t x : ev) (void)hipEventDestroy(x);   // destroying a recorded event is deferred by the runtime
-      ev.clear();
     }
   } groups;
   bool streamed = false, pipelined = false;
@@ -549,11 +595,9 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   if (any_host) {
     // the copies write k_buf / v_buf: they must not overtake earlier work of the compute
     // stream that still reads the buffers (the previous layer's attention)
-    hipEvent_t fence;
-    if ((e = hipEventCreateWithFlags(&fence, hipEventDisableTiming)) != hipSuccess) return hip_fail(e, "hipEventCreate");
+    hipEvent_t fence = ev_pool[0];
     e = hipEventRecord(fence, cs);
     if (e == hipSuccess) e = hipStreamWaitEvent(xs, fence, 0);
-    (void)hipEventDestroy(fence);
     if (e != hipSuccess) return hip_fail(e, "fence compute->copy stream");
     // Preferred: a kernel on the transfer stream reads the pinned chunks over the host link,
     // rotates the keys on the way and writes keys and values to their buffer rows (Eq. 8 overlapped
@@ -566,6 +610,7 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     pipelined = n_sel > 0 && host_chunks >= 2 && stream_in_skips_selected() &&
                 plan_attention(cfg, n_ctx, n_sel).n_splits == 1;
     groups.xs = xs;
+    groups.ev = ev_pool + 1;
     // Equal groups of chunks.  Without room for the attention state: as many as leave every
     // attention launch some 200 workgroups (a
     // launch computes the tiles of selected rows between two group ends, for every KV head; with
@@ -623,12 +668,8 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     }
     st = stream_in_host_chunks(cfg, chunks, n_chunks, tab, k_buf, v_buf, sel_idx, n_sel, xs, &streamed,
                                pipelined ? sizes : nullptr, n_groups, &GroupEvents::record, &groups);
-    if (st != CT_OK) {
-      groups.drop();
-      return st;
-    }
+    if (st != CT_OK) return st;
     if (!streamed && any_compact) return fail(CT_ERR_UNSUPPORTED, "compact pools are read by the stream-in kernel only");
-    landed.resize(n_chunks, nullptr);
     // Otherwise (host memory the device cannot address): plain copies, one event per chunk.
     for (int c = 0; c < n_chunks && !streamed; ++c) {
       const ct_chunk& ch = chunks[c];
@@ -638,20 +679,10 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
       const size_t bytes = (size_t)ch.n_tokens * row_bytes;
       e = hipMemcpyAsync(kd, ch.k, bytes, hipMemcpyHostToDevice, xs);
       if (e == hipSuccess) e = hipMemcpyAsync(vd, ch.v, bytes, hipMemcpyHostToDevice, xs);
-      if (e == hipSuccess) e = hipEventCreateWithFlags(&landed[c], hipEventDisableTiming);
       if (e == hipSuccess) e = hipEventRecord(landed[c], xs);
-      if (e != hipSuccess) {
-        for (hipEvent_t ev : landed)
-          if (ev) (void)hipEventDestroy(ev);
-        return hip_fail(e, "host->device chunk copy");
-      }
+      if (e != hipSuccess) return hip_fail(e, "host->device chunk copy");
     }
   }
-  auto drop_events = [&]() {
-    for (hipEvent_t ev : landed)
-      if (ev) (void)hipEventDestroy(ev);   // destroying a recorded event is deferred by the runtime
-    groups.drop();
-  };
 
   // The recomputed keys and values go straight from the projection's epilogue to their rows of
   // the layer buffers (the scatter of Sec. 4.2 fused into the GEMM) when nothing else writes those
@@ -661,12 +692,15 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
   // the workspace and a scatter launch follows the copies.
   const bool direct = n_sel > 0 && (!any_host || (streamed && stream_in_skips_selected()));
   // Device-resident chunks: rotated (and their values copied) into place in as few launches
-  // as the table size allows; they do not wait for any copy.
+  // as the table size allows; they do not wait for any copy.  Rows of the recompute set are left
+  // out: the projection's epilogue (or the scatter) writes them next.
   {
     ReropeChunks rc;
     auto flush = [&]() -> ct_status {
       if (rc.n == 0) return CT_OK;
       rc.tok_start[rc.n] = rc.total_tokens;
+      rc.skip_rows = n_sel > 0 ? sel_idx : nullptr;
+      rc.n_skip = n_sel;
       ct_status r = launch_rerope_chunks(cfg, k_buf, v_buf, &rc, 0, cs);
       rc.n = 0;
       rc.total_tokens = 0;
@@ -676,36 +710,25 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     for (int c = 0; c < n_chunks; ++c) {
       const ct_chunk& ch = chunks[c];
       if (ch.location != 0) continue;
-      const char* kd = static_cast<const char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;
       const char* vd = static_cast<const char*>(v_buf) + (size_t)tab.row_start[c] * row_bytes;
       const int i = rc.n++;
       rc.tok_start[i] = rc.total_tokens;
       rc.total_tokens += ch.n_tokens;
       rc.k_src[i] = ch.k;
       rc.v_src[i] = (ch.v == (const void*)vd) ? nullptr : ch.v;   // already in place: leave the values
-      (void)kd;
       rc.row_start[i] = tab.row_start[c];
       rc.delta0[i] = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
       rc.delta_step[i] = ch.raw_keys ? 1 : 0;
-      if (rc.n == 32 && (st = flush()) != CT_OK) {
-        drop_events();
-        return st;
-      }
+      if (rc.n == 32 && (st = flush()) != CT_OK) return st;
     }
-    if ((st = flush()) != CT_OK) {
-      drop_events();
-      return st;
-    }
+    if ((st = flush()) != CT_OK) return st;
   }
   // Recompute stream: projection of the selected rows runs while the copies are in flight.
   if (n_sel > 0) {
     st = direct ? launch_qkv(cfg, hidden, hidden_rows, nullptr, sel_idx, &tab, n_sel, wqkv, bias, q_rows, k_buf, v_buf, cs,
                              sel_idx)
                 : launch_qkv(cfg, hidden, hidden_rows, nullptr, sel_idx, &tab, n_sel, wqkv, bias, q_rows, k_rows, v_rows, cs);
-    if (st != CT_OK) {
-      drop_events();
-      return st;
-    }
+    if (st != CT_OK) return st;
   }
   // Pinned-host chunks: already rotated by the stream-in kernel, or rotated in place chunk by
   // chunk as soon as each copy has landed.
@@ -713,42 +736,30 @@ ct_status ct_partial_prefill_layer(const ct_layer_cfg* cfg, const ct_chunk* chun
     // The recomputed rows are not among those the stream-in kernel writes, so they are in their
     // slots already; one attention launch per group of chunks, each for the selected rows whose
     // last visible key that group completes.
-    st = CT_OK;
     int32_t seen = 0;
-    for (size_t j = 0; j < groups.ev.size() && st == CT_OK; ++j) {
-      if ((e = hipStreamWaitEvent(cs, groups.ev[j], 0)) != hipSuccess) {
-        st = hip_fail(e, "hipStreamWaitEvent (chunk group streamed in)");
-        break;
-      }
-      const int32_t upto = j + 1 == groups.ev.size() ? 0x7fffffff : tab.row_start[groups.last_chunk[j] + 1];
+    for (int j = 0; j < groups.n; ++j) {
+      if ((e = hipStreamWaitEvent(cs, groups.ev[j], 0)) != hipSuccess)
+        return hip_fail(e, "hipStreamWaitEvent (chunk group streamed in)");
+      const int32_t upto = j + 1 == groups.n ? 0x7fffffff : tab.row_start[groups.last_chunk[j] + 1];
       st = launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs, seen, upto,
                             attn_state);
+      if (st != CT_OK) return st;
       seen = upto;
     }
-    drop_events();
-    return st;
+    return CT_OK;
   }
-  if (streamed && !groups.ev.empty() && (e = hipStreamWaitEvent(cs, groups.ev.back(), 0)) != hipSuccess) {
-    drop_events();
+  if (streamed && groups.n > 0 && (e = hipStreamWaitEvent(cs, groups.ev[groups.n - 1], 0)) != hipSuccess)
     return hip_fail(e, "hipStreamWaitEvent (chunks streamed in)");
-  }
-  for (int c = 0; c < n_chunks && !streamed; ++c) {
+  for (int c = 0; c < n_chunks && any_host && !streamed; ++c) {
     const ct_chunk& ch = chunks[c];
     if (ch.location != 1) continue;
     char* kd = static_cast<char*>(k_buf) + (size_t)tab.row_start[c] * row_bytes;
-    e = hipStreamWaitEvent(cs, landed[c], 0);
-    if (e != hipSuccess) {
-      drop_events();
-      return hip_fail(e, "hipStreamWaitEvent (chunk landed)");
-    }
+    if ((e = hipStreamWaitEvent(cs, landed[c], 0)) != hipSuccess) return hip_fail(e, "hipStreamWaitEvent (chunk landed)");
     const int32_t d0 = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
-    st = launch_rerope(cfg, kd, kd, nullptr, nullptr, nullptr, nullptr, d0, ch.raw_keys ? 1 : 0, ch.n_tokens, cs);
-    if (st != CT_OK) {
-      drop_events();
+    // (rotates the chunk's stale selected rows too; the scatter below overwrites them)
+    if ((st = launch_rerope(cfg, kd, kd, nullptr, nullptr, nullptr, nullptr, d0, ch.raw_keys ? 1 : 0, ch.n_tokens, cs)) != CT_OK)
       return st;
-    }
   }
-  drop_events();
   if (n_sel == 0) return CT_OK;
   if (!direct && (st = launch_scatter(cfg, k_buf, v_buf, k_rows, v_rows, sel_idx, n_sel, cs)) != CT_OK) return st;
   return launch_attention(cfg, q_rows, k_buf, v_buf, n_ctx, sel_idx, n_sel, attn_out, nullptr, workspace, cs);

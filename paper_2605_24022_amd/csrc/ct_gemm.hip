@@ -112,8 +112,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
 
   // ---- workgroup -> tile, XCD aware (consecutive ids go to different XCDs) ----------------
   const int items = a.v_count * a.k_parts;
-  const int per_xcd = (items + 7) / 8;
-  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int per_xcd = (items + kNumXCDs - 1) / kNumXCDs;
+  const int item = (blockIdx.x % kNumXCDs) * per_xcd + blockIdx.x / kNumXCDs;
   if (item >= items) return;
   const int kp = item % a.k_parts;
   int f_tile, t_tile;
@@ -124,7 +124,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
   // ---- global -> LDS loads -------------------------------------------------------------------
   // load j of this wave fills LDS rows (NWAVES * j + wave) * 8 .. + 7 of the A (or B) tile; this
   // lane supplies physical piece lane % 8 of row lane / 8, i.e. logical piece (that ^ swizzle).
-  // Byte offsets from the tensor bases fit 32 bits (checked on the host); the K step advances
+  // Byte offsets from the tensor bases fit 32 bits (the entry points check the extents of the
+  // weights and of compact token matrices; gathered rows are the caller's contract); the K step advances
   // the scalar base, so the per-lane offsets are loop invariant.
   uint32_t a_off[A_LOADS], b_off[B_LOADS];
 #pragma unroll
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4,
   const uint32_t lds_addr0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
   auto dma16 = [&](const uint16_t* base, uint32_t byte_off, uint32_t lds_addr) __attribute__((always_inline)) {
     const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(byte_off), "s"(base) : "memory", "m0");
   };
   // A (weight) tiles cycle through three LDS slots, B (token) tiles through two.  `half` selects
   // the first or second half of a tile's loads.
@@ -482,7 +483,7 @@ static int pick_nb(const GemmArgs& a, bool swiglu) {
   for (int nb = 1; nb <= 2; ++nb) {
     fill_tiles(&t, swiglu, nb);
     const long wgs = (long)t.nF * t.nT;
-    cost[nb] = (double)((wgs + 255) / 256) * (nb == 2 ? 1.0 : 0.56);
+    cost[nb] = (double)((wgs + kNumCUs - 1) / kNumCUs) * (nb == 2 ? 1.0 : 0.56);
   }
   return cost[1] < cost[2] ? 1 : 2;
 }
@@ -491,8 +492,8 @@ template <typename Kernel>
 static ct_status launch_gemm(Kernel kernel, int threads, const GemmArgs& a, const RopeTable& rope, const ChunkTable& tab,
                              KernelClass kc, hipStream_t s) {
   const int items = a.v_count * a.k_parts;
-  const int per_xcd = (items + 7) / 8;
-  dim3 grid(per_xcd * 8), block(threads);
+  const int per_xcd = (items + kNumXCDs - 1) / kNumXCDs;
+  dim3 grid(per_xcd * kNumXCDs), block(threads);
   launch_kernel(kc, kernel, grid, block, 0, s, a, rope, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "gemm kernel launch");
@@ -587,7 +588,7 @@ size_t linear_workspace_bytes(int32_t n_tok, int32_t k_len, int32_t n_out) {
   fill_tiles(&a, false, 2);
   // at most one partial tile per compute unit, whatever share of the chip the launch is planned for
   const int tiles = a.nF * a.nT;
-  return (size_t)(tiles < 256 ? tiles * 8 < 256 ? tiles * 8 : 256 : 256) * 256 * BF * sizeof(float);
+  return (size_t)(tiles < kNumCUs ? tiles * 8 < kNumCUs ? tiles * 8 : kNumCUs : kNumCUs) * 256 * BF * sizeof(float);
 }
 
 ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void* w, int32_t n_out, const void* residual,
@@ -611,7 +612,7 @@ ct_status launch_linear(const void* x, int32_t n_tok, int32_t k_len, const void*
     GemmArgs t2 = a, t1 = a;
     fill_tiles(&t2, false, 2);
     fill_tiles(&t1, false, 1);
-    if (n_cu <= 0 || n_cu > 256) n_cu = 256;
+    if (n_cu <= 0 || n_cu > kNumCUs) n_cu = kNumCUs;
     const double c2 = (double)((t2.nF * t2.nT + n_cu - 1) / n_cu), c1 = 0.56 * (double)((t1.nF * t1.nT + n_cu - 1) / n_cu);
     int full = 0;
     const int parts = split_plan(t2, ws_bytes, c1 < c2 ? c1 : c2, n_cu, &full);

@@ -9,15 +9,31 @@
 
 namespace ct {
 
+// ---- the one chip this library is written for (MI355X, gfx950) --------------------------------
+constexpr int kNumCUs = 256;    // compute units
+constexpr int kNumXCDs = 8;     // accelerator dies; consecutive workgroup ids of a launch go to them in turn
+// Compute units a linear launch of the recompute stream should leave out of its plan for every
+// workgroup of the stream-in kernel that runs beside it (measured on the 32-layer stack: the
+// stream-in workgroups do not spread one per XCD, and the XCD with the fewest free units sets
+// the round).
+constexpr int kCUsHeldPerStreamInBlock = 4;
+
 // ---- kernel classes for the opt-in event profiling ------------------------------------
 enum KernelClass { KC_QKV = 0, KC_REROPE = 1, KC_SCATTER = 2, KC_ATTN = 3, KC_MERGE = 4, KC_LINEAR = 5, KC_NORM = 6, KC_FREQ = 7, KC_TOPK = 8, KC_COUNT = 9 };
 
 ct_status fail(ct_status code, const char* fmt, ...);
 ct_status hip_fail(hipError_t e, const char* what);
 ct_status check_cfg(const ct_layer_cfg* cfg);
+// K/V buffers of n_ctx rows must stay below 2^24 rows and 4 GiB (32-bit byte offsets in the attention kernel).
+ct_status check_kv_extent(const ct_layer_cfg* cfg, int64_t n_ctx);
 
 // A pair of events for one launch of class `kc` when profiling is on (both NULL when it is off).
 void prof_events(KernelClass kc, hipEvent_t* start, hipEvent_t* stop);
+
+// `n` timing-disabled events for stream ordering, reused from call to call (created on first use,
+// kept until the process ends, one set per calling thread).  Re-recording an event does not
+// disturb waits that were enqueued on its earlier record.
+ct_status pooled_events(size_t n, hipEvent_t** out);
 
 #if defined(__HIPCC__)
 // Every kernel of the library is launched through this.  With profiling on, the two events ride on
@@ -52,11 +68,15 @@ struct AttnPlan {
   size_t ws_bytes;   // workspace bytes needed
 };
 AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel);
+// Scratch bytes launch_attention needs behind its `workspace` pointer for this problem size.
+size_t attention_scratch_bytes(const ct_layer_cfg* cfg, int n_ctx, int n_sel);
 
 // ---- launchers implemented next to their kernels ---------------------------------------
+// skip_rows (optional, device memory, sorted ascending, n_skip entries): token rows that are neither
+// read nor written (the recompute set, whose keys the scatter overwrites).
 ct_status launch_rerope(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src, void* v_dst,
                         const int32_t* old_pos, const int32_t* new_pos, int32_t delta0, int32_t delta_step,
-                        int32_t n_tokens, hipStream_t s);
+                        int32_t n_tokens, hipStream_t s, const int32_t* skip_rows = nullptr, int32_t n_skip = 0);
 // Several device-resident chunks rotated (and their values copied) into the layer buffers
 // in one launch.  v_src[c] == NULL leaves the values of chunk c alone.
 struct ReropeChunks {
@@ -75,8 +95,9 @@ struct ReropeChunks {
 };
 // LDS that the small kernels of the recompute stream claim without using it (the large ones need
 // at least as much anyway): together with the 80 KiB the stream-in kernel claims, it keeps the two
-// streams' workgroups on different compute units.
-constexpr int kKeepOutLdsBytes = 96 * 1024;
+// streams' workgroups on different compute units.  It is asked for as dynamic LDS at the launch.
+constexpr unsigned kKeepOutLdsBytes = 96 * 1024;
+constexpr unsigned kStreamInLdsBytes = 80 * 1024;
 // max_blocks > 0 caps the grid (threads then stride over the tokens).
 ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
                                int max_blocks, hipStream_t s);

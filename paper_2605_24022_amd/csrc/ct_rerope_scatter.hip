@@ -111,17 +111,43 @@ __device__ __forceinline__ void rerope_token(const uint16_t* k_src, uint16_t* k_
   }
 }
 
+// Sorted skip lists (the recompute set: rows that are overwritten by the scatter and need not be
+// moved).  count_below: number of listed rows < row, by binary search.
+__device__ __forceinline__ int count_below(const int32_t* __restrict__ list, int n, int32_t row) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (list[mid] < row) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+// The rows of one workgroup lie next to each other: one search for the workgroup's first row
+// (the same for every thread, so its loads are scalar), then a walk over the few entries up to
+// this thread's row.  Rows far from the first one (a gap between chunks) search on their own.
+__device__ __forceinline__ int count_below_near(const int32_t* __restrict__ list, int n, int32_t first_row,
+                                                int first_below, int32_t row) {
+  if (row < first_row || row - first_row > 512) return count_below(list, n, row);
+  int i = first_below;
+  while (i < n && list[i] < row) ++i;
+  return i;
+}
+
 // Per-token positions, or one arithmetic progression of deltas (delta0 + delta_step * t).
 template <int D, int STYLE, int HEADS, bool NT_STORE>
 __global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
     const uint16_t* k_src, uint16_t* k_dst, const uint16_t* v_src, uint16_t* v_dst,
     const int32_t* __restrict__ old_pos, const int32_t* __restrict__ new_pos, int32_t delta0, int32_t delta_step,
-    int32_t n_tokens, int32_t n_heads_rt, RopeTable table) {
+    int32_t n_tokens, int32_t n_heads_rt, RopeTable table, const int32_t* __restrict__ skip_rows, int32_t n_skip) {
   constexpr int GROUPS = D / 16;  // threads per token: each owns 8 pairs = 16 elements per head
   const int64_t gid = (int64_t)blockIdx.x * kReropeThreads + threadIdx.x;
   const int64_t token = gid / GROUPS;
   const int jg = (int)(gid % GROUPS);
   if (token >= n_tokens) return;
+  if (skip_rows != nullptr) {
+    const int32_t first = (int32_t)((int64_t)blockIdx.x * (kReropeThreads / GROUPS));
+    const int at = count_below_near(skip_rows, n_skip, first, count_below(skip_rows, n_skip, first), (int32_t)token);
+    if (at < n_skip && skip_rows[at] == (int32_t)token) return;
+  }
   int32_t delta;
   if (new_pos != nullptr) {
     delta = new_pos[token] - (old_pos != nullptr ? old_pos[token] : 0);
@@ -134,32 +160,36 @@ __global__ __launch_bounds__(kReropeThreads) void rerope_kernel(
 }
 
 // Several chunks in one launch: buffer row -> chunk by search in the (small) table.
-template <int D, int STYLE, int HEADS>
+// NEAR: the grid covers every token once, so a workgroup's rows are neighbours and share one search
+// of the skip list; otherwise (few workgroups striding over the tokens) every token searches.
+template <int D, int STYLE, int HEADS, bool NEAR>
 __device__ __forceinline__ void rerope_chunk_tokens(uint16_t* k_buf, uint16_t* v_buf, int32_t n_heads_rt,
                                                     const RopeTable& table, const ReropeChunks& chunks, int threads) {
   constexpr int GROUPS = D / 16;
   const int64_t gid = (int64_t)blockIdx.x * threads + threadIdx.x;
   const int jg = (int)(gid % GROUPS);
   const int64_t t_step = (int64_t)gridDim.x * (threads / GROUPS);
+  int32_t first_row = 0;
+  int first_below = 0;
+  if (NEAR && chunks.skip_rows != nullptr) {
+    const int64_t t0 = (int64_t)blockIdx.x * (threads / GROUPS);   // the workgroup's first token
+    int c0 = 0;
+    while (c0 + 1 < chunks.n && t0 >= chunks.tok_start[c0 + 1]) ++c0;
+    first_row = chunks.row_start[c0] + (int32_t)(t0 - chunks.tok_start[c0]);
+    first_below = count_below(chunks.skip_rows, chunks.n_skip, first_row);
+  }
   for (int64_t t_all = gid / GROUPS; t_all < chunks.total_tokens; t_all += t_step) {   // ordinal among the listed tokens
     int c = 0;
     while (c + 1 < chunks.n && t_all >= chunks.tok_start[c + 1]) ++c;
     const int32_t t = (int32_t)(t_all - chunks.tok_start[c]);
     int32_t t_src = t;   // row inside the chunk's source
-    if (chunks.skip_rows != nullptr) {   // binary search for this buffer row in the sorted skip list
-      auto below = [&](int32_t row) {   // number of skipped rows < row
-        int lo = 0, hi = chunks.n_skip;
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (chunks.skip_rows[mid] < row) lo = mid + 1; else hi = mid;
-        }
-        return lo;
-      };
+    if (chunks.skip_rows != nullptr) {   // is this buffer row in the sorted skip list?
       const int32_t row = chunks.row_start[c] + t;
-      const int lo = below(row);
+      const int lo = NEAR ? count_below_near(chunks.skip_rows, chunks.n_skip, first_row, first_below, row)
+                          : count_below(chunks.skip_rows, chunks.n_skip, row);
       if (lo < chunks.n_skip && chunks.skip_rows[lo] == row) continue;
       // a compact source holds only the rows that are kept: step over the skipped ones before this row
-      if ((chunks.compact_mask >> c) & 1u) t_src = t - (lo - below(chunks.row_start[c]));
+      if ((chunks.compact_mask >> c) & 1u) t_src = t - (lo - count_below(chunks.skip_rows, chunks.n_skip, chunks.row_start[c]));
     }
     const int64_t heads = HEADS > 0 ? HEADS : n_heads_rt;
     const int64_t src_row = (int64_t)t_src * heads * D;
@@ -175,7 +205,7 @@ template <int D, int STYLE, int HEADS>
 __global__ __launch_bounds__(kReropeThreads) void rerope_chunks_kernel(uint16_t* k_buf, uint16_t* v_buf,
                                                                       int32_t n_heads_rt, RopeTable table,
                                                                       ReropeChunks chunks) {
-  rerope_chunk_tokens<D, STYLE, HEADS>(k_buf, v_buf, n_heads_rt, table, chunks, kReropeThreads);
+  rerope_chunk_tokens<D, STYLE, HEADS, true>(k_buf, v_buf, n_heads_rt, table, chunks, kReropeThreads);
 }
 
 // The same work for chunks in pinned host memory, read over the host link by a few resident
@@ -186,37 +216,24 @@ __global__ __launch_bounds__(kReropeThreads) void rerope_chunks_kernel(uint16_t*
 //    other kernels on the same compute unit, and L2 misses of any kernel in the same XCD, wait
 //    behind it.  So a thread keeps only one head's two 16-byte loads in flight (about 128 KiB
 //    over the whole grid already keeps the link at 45-50 GB/s; more only lengthens the queues);
-//  - the 80 KiB of LDS are not used: they keep the workgroups of the GEMM and attention kernels,
-//    which need 96-160 KiB, off the few compute units this kernel sits on, where they would run
-//    at the speed of the host link.
+//  - the launch asks for 80 KiB of (dynamic) LDS that the kernel does not use: they keep the
+//    workgroups of the GEMM and attention kernels, which need 96-160 KiB, off the few compute units
+//    this kernel sits on, where they would run at the speed of the host link.
 constexpr int kStreamInThreads = 1024;
-constexpr int kStreamInLdsBytes = 80 * 1024;
 template <int D, int STYLE>
 __global__ __launch_bounds__(kStreamInThreads) void stream_in_kernel(uint16_t* k_buf, uint16_t* v_buf, int32_t n_heads_rt,
                                                                     RopeTable table, ReropeChunks chunks) {
-  __shared__ unsigned char keep_out[kStreamInLdsBytes];
-  if (chunks.n < 0) {   // never true; keeps the allocation
-    keep_out[threadIdx.x * 64] = (unsigned char)threadIdx.x;
-    __syncthreads();
-    k_buf[threadIdx.x] = keep_out[(threadIdx.x * 64 + 64) % kStreamInLdsBytes];
-  }
-  rerope_chunk_tokens<D, STYLE, 0>(k_buf, v_buf, n_heads_rt, table, chunks, kStreamInThreads);
+  rerope_chunk_tokens<D, STYLE, 0, false>(k_buf, v_buf, n_heads_rt, table, chunks, kStreamInThreads);
 }
 
 // One 16-byte piece per thread and loop step; a selected row's K and V are `row_vec`
 // pieces each.  Pieces of consecutive threads are consecutive in memory.
-// The LDS is claimed, not used: see kKeepOutLdsBytes.
+// The launch asks for kKeepOutLdsBytes of dynamic LDS that the kernel does not use (see there).
 __global__ __launch_bounds__(1024) void scatter_kernel(u32x4* __restrict__ k_buf, u32x4* __restrict__ v_buf,
                                                       const u32x4* __restrict__ k_sel,
                                                       const u32x4* __restrict__ v_sel,
                                                       const int32_t* __restrict__ sel_idx, int32_t n_sel,
                                                       int32_t row_vec) {
-  __shared__ unsigned char keep_out[kKeepOutLdsBytes];
-  if (row_vec < 0) {   // never true; keeps the allocation
-    keep_out[threadIdx.x * 64] = (unsigned char)threadIdx.x;
-    __syncthreads();
-    k_buf[threadIdx.x][0] = keep_out[(threadIdx.x * 64 + 64) % kKeepOutLdsBytes];
-  }
   const int64_t total = (int64_t)n_sel * row_vec;
   for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (int64_t)gridDim.x * blockDim.x) {
     const int64_t s = p / row_vec;
@@ -229,41 +246,53 @@ __global__ __launch_bounds__(1024) void scatter_kernel(u32x4* __restrict__ k_buf
   }
 }
 
+// Arguments of the per-token form, bundled for the dispatch over (head_dim, style, head count).
+struct ReropeLaunch {
+  const uint16_t* ks; uint16_t* kd; const uint16_t* vs; uint16_t* vd;
+  const int32_t* old_pos; const int32_t* new_pos; int32_t delta0, delta_step, n_tokens;
+  const int32_t* skip_rows; int32_t n_skip;
+};
+
 template <int D, int STYLE, int HEADS>
-void launch_rerope_one(dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* kd, const uint16_t* vs, uint16_t* vd,
-                       const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep, int32_t n, int H,
-                       const RopeTable& t, const ReropeChunks* chunks, bool big_blocks) {
+void launch_rerope_one(dim3 grid, hipStream_t s, const ReropeLaunch& r, int H, const RopeTable& t,
+                       const ReropeChunks* chunks, bool big_blocks) {
   if (chunks != nullptr) {
     if (big_blocks)
-      launch_kernel(KC_REROPE, stream_in_kernel<D, STYLE>, grid, dim3(kStreamInThreads), 0, s, kd, vd, H, t, *chunks);
+      launch_kernel(KC_REROPE, stream_in_kernel<D, STYLE>, grid, dim3(kStreamInThreads), kStreamInLdsBytes, s, r.kd, r.vd,
+                    H, t, *chunks);
     else
-      launch_kernel(KC_REROPE, rerope_chunks_kernel<D, STYLE, HEADS>, grid, dim3(kReropeThreads), 0, s, kd, vd, H, t,
+      launch_kernel(KC_REROPE, rerope_chunks_kernel<D, STYLE, HEADS>, grid, dim3(kReropeThreads), 0, s, r.kd, r.vd, H, t,
                     *chunks);
   } else {
-    if (ks == kd)   // in place
-      launch_kernel(KC_REROPE, rerope_kernel<D, STYLE, HEADS, true>, grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
-                    np, d0, dstep, n, H, t);
+    if (r.ks == r.kd)   // in place
+      launch_kernel(KC_REROPE, rerope_kernel<D, STYLE, HEADS, true>, grid, dim3(kReropeThreads), 0, s, r.ks, r.kd, r.vs,
+                    r.vd, r.old_pos, r.new_pos, r.delta0, r.delta_step, r.n_tokens, H, t, r.skip_rows, r.n_skip);
     else
-      launch_kernel(KC_REROPE, rerope_kernel<D, STYLE, HEADS, false>, grid, dim3(kReropeThreads), 0, s, ks, kd, vs, vd, op,
-                    np, d0, dstep, n, H, t);
+      launch_kernel(KC_REROPE, rerope_kernel<D, STYLE, HEADS, false>, grid, dim3(kReropeThreads), 0, s, r.ks, r.kd, r.vs,
+                    r.vd, r.old_pos, r.new_pos, r.delta0, r.delta_step, r.n_tokens, H, t, r.skip_rows, r.n_skip);
   }
 }
 
 template <int D, int STYLE>
-void launch_rerope_heads(int H, dim3 grid, hipStream_t s, const uint16_t* ks, uint16_t* kd, const uint16_t* vs,
-                         uint16_t* vd, const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep, int32_t n,
-                         const RopeTable& t, const ReropeChunks* chunks, bool big_blocks) {
+void launch_rerope_heads(int H, dim3 grid, hipStream_t s, const ReropeLaunch& r, const RopeTable& t,
+                         const ReropeChunks* chunks, bool big_blocks) {
   if (H == 8)
-    launch_rerope_one<D, STYLE, 8>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks, big_blocks);
+    launch_rerope_one<D, STYLE, 8>(grid, s, r, H, t, chunks, big_blocks);
   else if (H == 2)
-    launch_rerope_one<D, STYLE, 2>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks, big_blocks);
+    launch_rerope_one<D, STYLE, 2>(grid, s, r, H, t, chunks, big_blocks);
   else
-    launch_rerope_one<D, STYLE, 0>(grid, s, ks, kd, vs, vd, op, np, d0, dstep, n, H, t, chunks, big_blocks);
+    launch_rerope_one<D, STYLE, 0>(grid, s, r, H, t, chunks, big_blocks);
 }
 
-ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_t* kd, const uint16_t* vs,
-                            uint16_t* vd, const int32_t* op, const int32_t* np, int32_t d0, int32_t dstep,
-                            int64_t n_tokens, const ReropeChunks* chunks, int max_blocks, hipStream_t s) {
+// The stream-in and scatter kernels are launched with more dynamic LDS than the default limit
+// of a kernel: raise the limit once per kernel.
+template <typename Kernel>
+hipError_t allow_dynamic_lds(Kernel kernel, unsigned bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+ct_status launch_rerope_any(const ct_layer_cfg* cfg, const ReropeLaunch& r, int64_t n_tokens, const ReropeChunks* chunks,
+                            int max_blocks, hipStream_t s) {
   if (n_tokens == 0) return CT_OK;
   RopeTable table;
   fill_rope_table(cfg, &table);
@@ -274,16 +303,26 @@ ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_
   int64_t blocks = (threads + per_block - 1) / per_block;
   if (big_blocks && blocks > max_blocks) blocks = max_blocks;
   dim3 grid((unsigned)blocks);
+  if (big_blocks) {
+    static const hipError_t allowed = []() {
+      hipError_t e = allow_dynamic_lds(stream_in_kernel<128, 0>, kStreamInLdsBytes);
+      if (e == hipSuccess) e = allow_dynamic_lds(stream_in_kernel<128, 1>, kStreamInLdsBytes);
+      if (e == hipSuccess) e = allow_dynamic_lds(stream_in_kernel<64, 0>, kStreamInLdsBytes);
+      if (e == hipSuccess) e = allow_dynamic_lds(stream_in_kernel<64, 1>, kStreamInLdsBytes);
+      return e;
+    }();
+    if (allowed != hipSuccess) return hip_fail(allowed, "hipFuncSetAttribute (stream-in kernel LDS)");
+  }
   if (D == 128) {
     if (cfg->rope_style == 0)
-      launch_rerope_heads<128, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
+      launch_rerope_heads<128, 0>(H, grid, s, r, table, chunks, big_blocks);
     else
-      launch_rerope_heads<128, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
+      launch_rerope_heads<128, 1>(H, grid, s, r, table, chunks, big_blocks);
   } else {
     if (cfg->rope_style == 0)
-      launch_rerope_heads<64, 0>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
+      launch_rerope_heads<64, 0>(H, grid, s, r, table, chunks, big_blocks);
     else
-      launch_rerope_heads<64, 1>(H, grid, s, ks, kd, vs, vd, op, np, d0, dstep, (int32_t)n_tokens, table, chunks, big_blocks);
+      launch_rerope_heads<64, 1>(H, grid, s, r, table, chunks, big_blocks);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "re-RoPE kernel launch");
@@ -294,28 +333,32 @@ ct_status launch_rerope_any(const ct_layer_cfg* cfg, const uint16_t* ks, uint16_
 
 ct_status launch_rerope(const ct_layer_cfg* cfg, const void* k_src, void* k_dst, const void* v_src, void* v_dst,
                         const int32_t* old_pos, const int32_t* new_pos, int32_t delta0, int32_t delta_step,
-                        int32_t n_tokens, hipStream_t s) {
-  return launch_rerope_any(cfg, static_cast<const uint16_t*>(k_src), static_cast<uint16_t*>(k_dst),
-                           static_cast<const uint16_t*>(v_src), static_cast<uint16_t*>(v_dst), old_pos, new_pos,
-                           delta0, delta_step, n_tokens, nullptr, 0, s);
+                        int32_t n_tokens, hipStream_t s, const int32_t* skip_rows, int32_t n_skip) {
+  ReropeLaunch r = {static_cast<const uint16_t*>(k_src), static_cast<uint16_t*>(k_dst), static_cast<const uint16_t*>(v_src),
+                    static_cast<uint16_t*>(v_dst), old_pos, new_pos, delta0, delta_step, n_tokens,
+                    n_skip > 0 ? skip_rows : nullptr, n_skip};
+  return launch_rerope_any(cfg, r, n_tokens, nullptr, 0, s);
 }
 
 ct_status launch_rerope_chunks(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const ReropeChunks* chunks,
                                int max_blocks, hipStream_t s) {
-  return launch_rerope_any(cfg, nullptr, static_cast<uint16_t*>(k_buf), nullptr, static_cast<uint16_t*>(v_buf),
-                           nullptr, nullptr, 0, 0, chunks->total_tokens, chunks, max_blocks, s);
+  ReropeLaunch r = {nullptr, static_cast<uint16_t*>(k_buf), nullptr, static_cast<uint16_t*>(v_buf), nullptr, nullptr, 0, 0, 0,
+                    nullptr, 0};
+  return launch_rerope_any(cfg, r, chunks->total_tokens, chunks, max_blocks, s);
 }
 
 ct_status launch_scatter(const ct_layer_cfg* cfg, void* k_buf, void* v_buf, const void* k_sel, const void* v_sel,
                          const int32_t* sel_idx, int32_t n_sel, hipStream_t s) {
   if (n_sel == 0) return CT_OK;
+  static const hipError_t allowed = allow_dynamic_lds(scatter_kernel, kKeepOutLdsBytes);
+  if (allowed != hipSuccess) return hip_fail(allowed, "hipFuncSetAttribute (scatter kernel LDS)");
   const int row_vec = cfg->n_kv_heads * cfg->head_dim / 8;  // 16-byte pieces per row
   const int64_t total = (int64_t)n_sel * row_vec;
   int64_t blocks = (total + 1023) / 1024;
   if (blocks > 2048) blocks = 2048;
-  launch_kernel(KC_SCATTER, scatter_kernel, dim3((unsigned)blocks), dim3(1024), 0, s, static_cast<u32x4*>(k_buf),
-                static_cast<u32x4*>(v_buf), static_cast<const u32x4*>(k_sel), static_cast<const u32x4*>(v_sel),
-                sel_idx, n_sel, row_vec);
+  launch_kernel(KC_SCATTER, scatter_kernel, dim3((unsigned)blocks), dim3(1024), kKeepOutLdsBytes, s,
+                static_cast<u32x4*>(k_buf), static_cast<u32x4*>(v_buf), static_cast<const u32x4*>(k_sel),
+                static_cast<const u32x4*>(v_sel), sel_idx, n_sel, row_vec);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "scatter kernel launch");
   return CT_OK;

@@ -8,9 +8,6 @@
 // overhead"; steady-state cost model Eq. 10).
 #include <string.h>
 
-#include <mutex>
-#include <vector>
-
 #include "ct_internal.h"
 
 namespace ct {
@@ -18,20 +15,15 @@ namespace ct {
 namespace {
 
 // One wave per row: sum of squares in fp32, wave reduction, second pass scales and rounds.
-// The LDS is not used: claiming it keeps the workgroups off the compute units on which the
-// stream-in kernel of the transfer stream sits (which claims the other half), where every memory
-// access would wait behind that kernel's loads from host memory.
+// The launch asks for kKeepOutLdsBytes of dynamic LDS that the kernel does not use: that keeps the
+// workgroups off the compute units on which the stream-in kernel of the transfer stream sits (which
+// claims the other half), where every memory access would wait behind that kernel's loads from host
+// memory.
 constexpr int kNormRows = 16;
 __global__ __launch_bounds__(64 * kNormRows) void rmsnorm_kernel(const uint16_t* __restrict__ x,
                                                                 const uint16_t* __restrict__ w,
                                                                 uint16_t* __restrict__ out, int32_t n_tok, int32_t width,
                                                                 float eps) {
-  __shared__ unsigned char keep_out[kKeepOutLdsBytes];
-  if (width < 0) {   // never true; keeps the allocation
-    keep_out[threadIdx.x * 64] = (unsigned char)threadIdx.x;
-    __syncthreads();
-    out[threadIdx.x] = keep_out[(threadIdx.x * 64 + 64) % kKeepOutLdsBytes];
-  }
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * kNormRows + (threadIdx.x >> 6);
   if (row >= n_tok) return;
@@ -60,22 +52,6 @@ __global__ __launch_bounds__(64 * kNormRows) void rmsnorm_kernel(const uint16_t*
       r[i] = pack_bf16(bf16_lo(v[i]) * scale * bf16_lo(g[i]), bf16_hi(v[i]) * scale * bf16_hi(g[i]));
     orow[p] = r;
   }
-}
-
-// Events reused across calls (created on first use, kept for the life of the process).
-std::mutex g_ev_mu;
-std::vector<hipEvent_t> g_ev_pool;
-
-ct_status acquire_events(size_t n, std::vector<hipEvent_t>* out) {
-  std::lock_guard<std::mutex> lk(g_ev_mu);
-  while (g_ev_pool.size() < n) {
-    hipEvent_t e;
-    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
-    if (err != hipSuccess) return hip_fail(err, "hipEventCreate");
-    g_ev_pool.push_back(e);
-  }
-  out->assign(g_ev_pool.begin(), g_ev_pool.begin() + n);
-  return CT_OK;
 }
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -108,7 +84,10 @@ StackLayout stack_layout(const ct_layer_cfg* cfg, int32_t ffn_dim, int32_t n_ctx
 
 ct_status launch_rmsnorm(const void* x, const void* w, float eps, int32_t n_tok, int32_t width, void* out, hipStream_t s) {
   if (n_tok == 0) return CT_OK;
-  launch_kernel(KC_NORM, rmsnorm_kernel, dim3((n_tok + kNormRows - 1) / kNormRows), dim3(64 * kNormRows), 0, s,
+  static const hipError_t allowed = hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_kernel),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kKeepOutLdsBytes);
+  if (allowed != hipSuccess) return hip_fail(allowed, "hipFuncSetAttribute (rmsnorm kernel LDS)");
+  launch_kernel(KC_NORM, rmsnorm_kernel, dim3((n_tok + kNormRows - 1) / kNormRows), dim3(64 * kNormRows), kKeepOutLdsBytes, s,
                 static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(out), n_tok, width,
                 eps);
   hipError_t e = hipGetLastError();
@@ -149,7 +128,7 @@ ct_status ct_linear(const void* x, int32_t n_tokens, int32_t k_len, const void* 
   if (!x || !w || !out) return fail(CT_ERR_NULL, "x, w and out must be non-NULL");
   if ((((uintptr_t)x | (uintptr_t)w | (uintptr_t)out | (uintptr_t)residual) & 15) != 0)
     return fail(CT_ERR_UNSUPPORTED, "x, w, residual and out must be 16-byte aligned");
-  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, nullptr, 0, 256, static_cast<hipStream_t>(stream));
+  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, nullptr, 0, kNumCUs, static_cast<hipStream_t>(stream));
 }
 
 size_t ct_linear_workspace_bytes(int32_t n_tokens, int32_t k_len, int32_t n_out) {
@@ -159,15 +138,22 @@ size_t ct_linear_workspace_bytes(int32_t n_tokens, int32_t k_len, int32_t n_out)
 
 ct_status ct_linear_ws(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out, const void* residual,
                        void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return ct_linear_ws_cus(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, kNumCUs, stream);
+}
+
+ct_status ct_linear_ws_cus(const void* x, int32_t n_tokens, int32_t k_len, const void* w, int32_t n_out, const void* residual,
+                           void* out, void* workspace, size_t workspace_bytes, int32_t n_compute_units, void* stream) {
   ct_status st = check_gemm_shape(n_tokens, k_len, n_out);
   if (st != CT_OK) return st;
+  if (n_compute_units < 1 || n_compute_units > kNumCUs)
+    return fail(CT_ERR_SHAPE, "n_compute_units %d is outside [1, %d]", n_compute_units, kNumCUs);
   if (n_tokens == 0) return CT_OK;
   if (!x || !w || !out) return fail(CT_ERR_NULL, "x, w and out must be non-NULL");
   if ((((uintptr_t)x | (uintptr_t)w | (uintptr_t)out | (uintptr_t)residual) & 15) != 0)
     return fail(CT_ERR_UNSUPPORTED, "x, w, residual and out must be 16-byte aligned");
   if (workspace != nullptr && ((uintptr_t)workspace & 15) != 0)
     return fail(CT_ERR_WORKSPACE, "workspace is not 16-byte aligned");
-  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, 256,
+  return launch_linear(x, n_tokens, k_len, w, n_out, residual, out, workspace, workspace_bytes, n_compute_units,
                        static_cast<hipStream_t>(stream));
 }
 
@@ -191,6 +177,16 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
                                    int32_t n_layers, int32_t n_chunks, void* hidden_sel, const int32_t* sel_idx,
                                    int32_t n_sel, double recompute_ratio, void* k_bufs, void* v_bufs, void* workspace,
                                    size_t workspace_bytes, void* compute_stream, void* copy_stream) {
+  return ct_partial_prefill_stack_tap(cfg, ffn_dim, rms_eps, layers, n_layers, n_chunks, hidden_sel, sel_idx, n_sel,
+                                      recompute_ratio, k_bufs, v_bufs, workspace, workspace_bytes, compute_stream,
+                                      copy_stream, nullptr);
+}
+
+ct_status ct_partial_prefill_stack_tap(const ct_layer_cfg* cfg, int32_t ffn_dim, float rms_eps,
+                                       const ct_layer_weights* layers, int32_t n_layers, int32_t n_chunks,
+                                       void* hidden_sel, const int32_t* sel_idx, int32_t n_sel, double recompute_ratio,
+                                       void* k_bufs, void* v_bufs, void* workspace, size_t workspace_bytes,
+                                       void* compute_stream, void* copy_stream, void* layer_inputs) {
   ct_status st = check_cfg(cfg);
   if (st != CT_OK) return st;
   if (layers == nullptr) return fail(CT_ERR_NULL, "layers is NULL");
@@ -243,8 +239,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
       for (int c = 0; c < n_chunks; ++c)
         if (!layers[l].chunks[c].k || !layers[l].chunks[c].v) return fail(CT_ERR_NULL, "layer %d chunk %d has a NULL k or v", l, c);
   }
-  if ((uint64_t)n_ctx * cfg->n_kv_heads * cfg->head_dim * 2 > 0xffffffffull)
-    return fail(CT_ERR_UNSUPPORTED, "K/V buffers beyond 4 GiB each (n_ctx %d) are not supported", n_ctx);
+  if ((st = check_kv_extent(cfg, n_ctx)) != CT_OK) return st;
   if (recompute_ratio >= 0.0) {
     if (!(recompute_ratio <= 1.0)) return fail(CT_ERR_RATIO, "recompute_ratio %g is above 1", recompute_ratio);
     int64_t want = (int64_t)floor(recompute_ratio * (double)n_ctx + 1e-9);
@@ -271,8 +266,8 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
   const int32_t qd = cfg->n_q_heads * cfg->head_dim;
 
   // events: one "landed" per (layer parity, chunk), one "attention done" per layer parity, one fence
-  std::vector<hipEvent_t> ev;
-  st = acquire_events((size_t)2 * n_chunks + 3, &ev);
+  hipEvent_t* ev = nullptr;
+  st = pooled_events((size_t)2 * n_chunks + 3, &ev);
   if (st != CT_OK) return st;
   auto landed = [&](int l, int c) { return ev[(size_t)(l & 1) * n_chunks + c]; };
   auto attn_done = [&](int l) { return ev[(size_t)2 * n_chunks + (l & 1)]; };
@@ -322,6 +317,11 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     if (l + 1 < n_layers && (st = enqueue_copies(l + 1)) != CT_OK) return st;
     char* kb = static_cast<char*>(k_bufs) + (size_t)(l & 1) * buf_bytes;
     char* vb = static_cast<char*>(v_bufs) + (size_t)(l & 1) * buf_bytes;
+    if (layer_inputs != nullptr) {   // hand out the rows as they enter this layer
+      const size_t bytes = (size_t)n_sel * cfg->hidden * 2;
+      e = hipMemcpyAsync(static_cast<char*>(layer_inputs) + (size_t)l * bytes, hidden_sel, bytes, hipMemcpyDeviceToDevice, cs);
+      if (e != hipSuccess) return hip_fail(e, "copy of a layer's input rows");
+    }
 
     // attention block on the selected rows
     if ((st = launch_rmsnorm(hidden_sel, lw.attn_norm, rms_eps, n_sel, cfg->hidden, ws + L.x_norm, cs)) != CT_OK) return st;
@@ -337,6 +337,8 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
       auto flush = [&]() -> ct_status {
         if (rc.n == 0) return CT_OK;
         rc.tok_start[rc.n] = rc.total_tokens;
+        rc.skip_rows = sel_idx;   // the projection's epilogue (or the scatter) overwrites these rows next
+        rc.n_skip = n_sel;
         ct_status r = launch_rerope_chunks(cfg, kb, vb, &rc, 0, cs);
         rc.n = 0;
         rc.total_tokens = 0;
@@ -372,7 +374,7 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
         char* kd = kb + (size_t)tab.row_start[c] * row_bytes;
         const int32_t d0 = ch.raw_keys ? ch.new_pos_start : ch.new_pos_start - ch.old_pos_start;
         if ((st = launch_rerope(cfg, kd, kd, nullptr, nullptr, nullptr, nullptr, d0, ch.raw_keys ? 1 : 0, ch.n_tokens, cs)) != CT_OK)
-          return st;
+          return st;   // (rotates the chunk's stale selected rows too; the scatter below overwrites them)
       }
     }
     if (!direct && (st = launch_scatter(cfg, kb, vb, ws + L.k, ws + L.v, sel_idx, n_sel, cs)) != CT_OK) return st;
@@ -385,8 +387,9 @@ ct_status ct_partial_prefill_stack(const ct_layer_cfg* cfg, int32_t ffn_dim, flo
     // rounds are planned for what is left.  A launch's workgroups go to the eight XCDs in turn, so
     // what counts is the XCD with the fewest free units, and the stream-in workgroups do not
     // spread one per XCD: with 8 of them, launches planned for 216-224 units (28 per XCD) finish
-    // in one round, launches planned for 232 or more do not (measured on the config-5 stack).
-    const int gemm_cus = (l + 2 < n_layers && (streamed[0] || streamed[1])) ? 256 - 4 * stream_in_blocks() : 256;
+    // in one round, launches planned for 232 or more do not (measured on the 32-layer stack).
+    const int gemm_cus = (l + 2 < n_layers && (streamed[0] || streamed[1]))
+                             ? kNumCUs - kCUsHeldPerStreamInBlock * stream_in_blocks() : kNumCUs;
     if ((st = launch_linear(ws + L.attn_out, n_sel, qd, lw.wo, cfg->hidden, hidden_sel, hidden_sel, ws + L.gemm_ws,
                             L.gemm_ws_bytes, gemm_cus, cs)) != CT_OK) return st;
     if ((st = launch_rmsnorm(hidden_sel, lw.ffn_norm, rms_eps, n_sel, cfg->hidden, ws + L.x_norm, cs)) != CT_OK) return st;

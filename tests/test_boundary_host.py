@@ -76,6 +76,33 @@ def test_null_and_shape_errors():
     B.ct_selected_attention(c, None, None, None, 64, None, 0, None, None, None, 0)
 
 
+def test_extent_limits_are_rejected_on_the_host():
+    """32-bit byte offsets and 24-bit row numbers inside the kernels: sizes beyond them are errors."""
+    small = B.make_cfg(64, 1, 1, 64, 1e4)                    # 128-byte K/V rows: 2^24 rows stay below 4 GiB
+    assert _status(B.ct_selected_attention, small, FAKE, FAKE, FAKE, 1 << 24, FAKE, 4, FAKE, None, FAKE, 1 << 30) \
+        == B.CT_ERR_UNSUPPORTED
+    c = _cfg()
+    assert _status(B.ct_selected_attention, c, FAKE, FAKE, FAKE, 1 << 21, FAKE, 4, FAKE, None, FAKE, 1 << 30) \
+        == B.CT_ERR_UNSUPPORTED                                 # 2^21 rows x 2 KiB = 4 GiB
+    # compact hidden of n_sel rows x 4096 x 2 bytes beyond 4 GiB
+    assert _status(B.ct_qkv_selected, c, FAKE, None, FAKE, 1 << 19, FAKE, None, FAKE, FAKE, FAKE) == B.CT_ERR_UNSUPPORTED
+    wide = B.make_cfg(1 << 17, 128, 128, 128, 1e4)            # wqkv of 49152 x 131072 x 2 bytes
+    assert _status(B.ct_qkv_selected, wide, FAKE, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, FAKE) == B.CT_ERR_UNSUPPORTED
+
+
+def test_rerope_skip_and_planned_linear_validation():
+    c = _cfg()
+    assert _status(B.ct_rerope_keys_skip, c, FAKE, FAKE, None, FAKE, 16, None, 4) == B.CT_ERR_NULL
+    assert _status(B.ct_rerope_keys_skip, c, FAKE, FAKE, None, FAKE, 16, FAKE, 17) == B.CT_ERR_SHAPE
+    assert _status(B.ct_rerope_keys_skip, c, FAKE, FAKE, None, FAKE, 16, FAKE, -1) == B.CT_ERR_SHAPE
+    assert _status(B.ct_rerope_keys_skip, c, None, FAKE, None, FAKE, 16, FAKE, 4) == B.CT_ERR_NULL
+    B.ct_rerope_keys_skip(c, None, None, None, None, 0, None, 0)
+    assert _status(B.ct_linear_ws_cus, FAKE, 4, 512, FAKE, 512, None, FAKE, FAKE, 1 << 20, 0) == B.CT_ERR_SHAPE
+    assert _status(B.ct_linear_ws_cus, FAKE, 4, 512, FAKE, 512, None, FAKE, FAKE, 1 << 20, 257) == B.CT_ERR_SHAPE
+    assert _status(B.ct_linear_ws_cus, FAKE, 4, 512, None, 512, None, FAKE, FAKE, 1 << 20, 224) == B.CT_ERR_NULL
+    B.ct_linear_ws_cus(None, 0, 512, None, 512, None, None, None, 0, 224)
+
+
 def test_attention_workspace_checks():
     c = _cfg()
     need = B.ct_workspace_bytes(c, 32768, 1638)   # few tiles -> split keys -> partials in the workspace

@@ -18,9 +18,13 @@ def _need_gpu():
     torch.cuda.set_device(0)
 
 
-@pytest.mark.parametrize("ratio", [15, 5])
+@pytest.mark.parametrize("ratio", [15, 5, 10, 30])
 def test_layer_config3_sampled_rows(ratio):
-    """32768-token context; r = 15 % is the headline point, r = 5 % exercises key-range splits."""
+    """32768-token context, the ratio sweep: r = 15 % is the headline point, r = 5 % exercises
+    key-range splits.  The attention output is checked on 192 sampled selected rows (first, last,
+    middle and a seeded uniform fill; a row's output depends on no other query), the fused K and V
+    buffers are checked whole.  The full row set at r = 15 % would cost the oracle about 40 s more
+    per case than the sample does; the sample is what keeps the GPU suite within minutes."""
     wl = W.make_workload(W.spec(3, ratio))
     out, kb, vb = _run_layer(wl)
     rows = W.sample_rows(wl.spec.n_sel, 192, seed=ratio)
@@ -61,6 +65,17 @@ def test_layer_config3_host_pools_attention_follows_the_chunk_groups(pool, state
     assert torch.isfinite(out.float()).all()        # every tile was computed by exactly one of the launches
 
 
+@pytest.mark.parametrize("pool", ["pinned", "compact"])
+def test_layer_config3_raw_key_cache_in_host_memory(pool):
+    """The paper's cache scheme at full size (Eq. 8): pre-RoPE keys in a host pool, rotated by their
+    global positions on the way in; the compact pool must take the position of the row a pool row
+    stands for.  Attention follows the chunk groups key range by key range."""
+    wl = W.make_workload(W.spec(3, 15))
+    out, kb, vb = _run_layer(wl, pinned=pool == "pinned", compact=pool == "compact", state=True, raw=True)
+    rows = W.sample_rows(wl.spec.n_sel, 96, seed=34)
+    _check_layer(wl, out, kb, vb, rows=rows, raw=True)
+
+
 def test_layer_config2_compact_host_pool():
     """8192-token context, forced + uniform rows; the host pool holds only the rows that are reused."""
     wl = W.make_workload(W.spec(2))
@@ -91,3 +106,67 @@ def test_stack_config5_one_layer_sampled_rows():
                                             sh.rope_style, rows=rows)
     want = O.layer_tail(h0[rows], attn, lw["wo"], lw["ffn_norm"], lw["w_gate"], lw["w_up"], lw["w_down"], sw.rms_eps)
     assert_close(f64_of(h)[rows], want, "config-5 layer output (sampled rows)", ulp_slack=2.0 ** -8)
+
+
+def test_stack_config5_32_layers_one_call_teacher_forced():
+    """The launch configuration `bench.py --config 5` times: 32 Llama-3-8B-shaped layers (hidden 4096,
+    FFN 14336, 32768-token context, r = 15 %, cached K/V in pinned host memory) in ONE stack call, so
+    that the transfer of layer l + 2 runs beside the GEMMs of layer l, which are planned for the
+    compute units it leaves (whole rounds + a split last round), and both buffer slots are reused.
+    Four distinct layers (weights and caches) repeat eight times.  Layers 0, 1, 15 and 31 are checked
+    teacher-forced: the oracle gets the rows the GPU fed that layer (handed out by the call) and its
+    output is compared on sampled rows at the single-layer bounds."""
+    from oracle import ct_oracle as O
+    from paper_2605_24022_amd import binding as B
+    from tests.gpu_util import assert_close, bits_of, dev_bf16, dev_i32, f64_of, pinned_bf16
+
+    n_layers, distinct, ffn = 32, 4, 14336
+    sp = W.spec(5)
+    sh = sp.shape
+    say(f"generating {distinct} distinct layers of the config-5 stack")
+    sw = W.make_stack_workload(sp, n_layers=distinct, ffn_dim=ffn)
+    cfg = B.cfg_from_shape(sh)
+    n_ctx, n_sel, E = sp.n_ctx, sp.n_sel, sh.hidden
+    dev_layers, keep = [], []
+    for lw in sw.layers:
+        d = {k: dev_bf16(lw[k]) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")}
+        kc, vc = lw["k_cache"].copy(), lw["v_cache"].copy()
+        kc[sw.sel_idx] = 0x7FC0          # stale rows at the selected slots must never be read
+        vc[sw.sel_idx] = 0x7FC0
+        kp, vp = pinned_bf16(kc), pinned_bf16(vc)
+        ch = B.make_chunks([dict(k=kp[int(sw.chunk_rows[c]):int(sw.chunk_rows[c + 1])],
+                                 v=vp[int(sw.chunk_rows[c]):int(sw.chunk_rows[c + 1])],
+                                 n_tokens=int(sw.chunk_rows[c + 1] - sw.chunk_rows[c]), old_pos_start=0,
+                                 new_pos_start=int(sw.chunk_new_start[c]), location=1) for c in range(sp.n_chunks)])
+        keep.append((kp, vp, ch))
+        d["chunks"] = ch
+        dev_layers.append(d)
+    layers = B.make_layers([dev_layers[l % distinct] for l in range(n_layers)])
+    ws_bytes = B.ct_stack_workspace_bytes(cfg, ffn, n_ctx, n_sel)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    k_bufs = torch.full((2, n_ctx, sh.n_kv_heads, sh.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v_bufs = torch.full_like(k_bufs, float("nan"))
+    h = dev_bf16(sw.hidden0).clone()
+    tap = torch.full((n_layers, n_sel, E), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    say(f"stack {sp.name}: {n_layers} layers in one call, n_ctx={n_ctx} n_sel={n_sel} ffn={ffn}, pinned pool")
+    B.ct_partial_prefill_stack_tap(cfg, ffn, sw.rms_eps, layers, n_layers, sp.n_chunks, h, dev_i32(sw.sel_idx), n_sel,
+                                   sp.ratio_pct / 100.0, k_bufs, v_bufs, ws, ws_bytes, s1, s2, tap)
+    torch.cuda.synchronize()
+    assert torch.isfinite(h.float()).all() and torch.isfinite(tap.float()).all()
+    assert np.array_equal(bits_of(tap[0]), sw.hidden0)
+    rows = W.sample_rows(n_sel, 48, seed=55)
+    for l in (0, 1, 15, 31):
+        say(f"oracle for layer {l}: projections of {n_sel} rows, attention and FFN of {len(rows)} sampled rows")
+        lw = {k: W.bf16_bits_to_f64(v) for k, v in sw.layers[l % distinct].items()}
+        h_in = f64_of(tap[l])
+        h_out = f64_of(tap[l + 1] if l + 1 < n_layers else h)
+        x = O.rmsnorm(h_in, lw["attn_norm"], sw.rms_eps)
+        attn, _, _, _ = O.partial_prefill_layer(x, lw["wqkv"], None, lw["k_cache"], lw["v_cache"], sw.old_pos, sw.new_pos,
+                                                sw.sel_idx, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta,
+                                                sh.rope_style, rows=rows)
+        want = O.layer_tail(h_in[rows], attn, lw["wo"], lw["ffn_norm"], lw["w_gate"], lw["w_up"], lw["w_down"], sw.rms_eps)
+        assert_close(h_out[rows], want, f"layer {l} of 32 (teacher forced, sampled rows)", ulp_slack=2.0 ** -8,
+                     unit_scale_rows=True)
+        del lw

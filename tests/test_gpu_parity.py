@@ -72,6 +72,40 @@ def test_rerope_chunk_with_value_copy(raw):
     assert np.array_equal(bits_of(vo), v_bits)
 
 
+@pytest.mark.parametrize("Hkv,D,style,in_place", [(8, 128, 0, True), (8, 128, 0, False), (2, 64, 1, True), (3, 64, 0, False)])
+def test_rerope_keys_skip_leaves_the_recompute_set_alone(Hkv, D, style, in_place):
+    """Rows of the skip list are neither read nor written; every other row is rotated as by
+    ct_rerope_keys.  The list has dense runs, isolated rows, the first and the last row."""
+    n = 5000 + 13
+    rng = np.random.default_rng([18, Hkv, D, style])
+    k_bits = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, D), dtype=np.float32))
+    old = rng.integers(0, 4096, n).astype(np.int32)
+    new = rng.integers(0, 131072, n).astype(np.int32)
+    skip = np.unique(np.concatenate([[0, n - 1], np.arange(100, 420), np.arange(2047, 2050),
+                                     rng.choice(n, 600, replace=False)])).astype(np.int32)
+    k_bits[skip] = 0x7FC0                       # whatever stands in skipped rows must not matter ...
+    cfg = B.make_cfg(Hkv * D * 2, Hkv * 2, Hkv, D, 5e5, style)
+    say(f"rerope with skip list Hkv={Hkv} D={D} style={style} in_place={in_place} n={n} n_skip={skip.size}")
+    k = dev_bf16(k_bits)
+    out = k if in_place else torch.full_like(k, -7.0)
+    B.ct_rerope_keys_skip(cfg, k, out, dev_i32(old), dev_i32(new), n, dev_i32(skip), skip.size)
+    torch.cuda.synchronize()
+    keep = np.setdiff1d(np.arange(n), skip)
+    want = O.rerope_keys(W.bf16_bits_to_f64(k_bits[keep]), old[keep], new[keep], 5e5, style)
+    # one rounding to bf16 per element: 2^-9 relative on average rows, up to 2^-8 for a row whose
+    # elements all sit at the bottom of their binades; short rows (3 x 64) scatter more than long ones
+    assert_close(f64_of(out)[keep], want, "rerope (kept rows)", rel_l2=3e-3)
+    got_skip = bits_of(out)[skip]               # ... and those rows are not written
+    assert np.array_equal(got_skip, k_bits[skip] if in_place else np.full_like(got_skip, 0xC0E0))
+    # an empty list is ct_rerope_keys
+    a, b = torch.empty_like(k), torch.empty_like(k)
+    k2 = dev_bf16(W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, D), dtype=np.float32)))
+    B.ct_rerope_keys_skip(cfg, k2, a, dev_i32(old), dev_i32(new), n, None, 0)
+    B.ct_rerope_keys(cfg, k2, b, dev_i32(old), dev_i32(new), n)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
 # ------------------------------------------------------------------------------ scatter
 @pytest.mark.parametrize("Hkv,D", [(2, 64), (8, 128)])
 def test_scatter_bit_exact(Hkv, D):
@@ -176,6 +210,9 @@ def _attention_case(Hq, Hkv, D, n_ctx, sel, seed, rows=None, want_split=None, tr
     (32, 8, 128, 2048, 307, 3),      # Llama head layout
     (4, 4, 128, 700, 50, 4),         # G = 1: 256-token tiles
     (16, 2, 128, 900, 77, 5),        # G = 8: 32-token tiles
+    (4, 2, 128, 1500, 300, 8),       # G = 2: 128-token tiles
+    (16, 1, 64, 1100, 40, 9),        # G = 16: 16-token tiles, one KV head
+    (32, 2, 128, 3000, 90, 10),      # G = 16, D = 128, several tiles
     (32, 8, 128, 777, 1, 6),         # a single selected row
     (32, 8, 128, 8192, 400, 7),      # few tiles, long context -> key-range splits + merge
 ])
@@ -210,8 +247,12 @@ def test_selected_attention_drifting_maximum(trend):
 
 
 # ------------------------------------------------------------------------------ whole layer
-def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False, mixed=False, state=False):
+def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, compact=False, mixed=False, state=False,
+               raw=False):
+    """raw: the pool holds keys cached before RoPE (the paper's own scheme, Eq. 8): chunks are
+    passed with raw_keys = 1 and the oracle rotates from position 0."""
     sp, sh = wl.spec, wl.spec.shape
+    n_chunks = len(wl.chunk_rows) - 1
     cfg = B.cfg_from_shape(sh)
     n_ctx, n_sel = sp.n_ctx, sp.n_sel
     hidden = dev_bf16(wl.hidden)
@@ -239,20 +280,20 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, co
     else:
         k_pool, v_pool = dev_bf16(k_cache), dev_bf16(v_cache)
     entries, keep_alive = [], []
-    for c in range(sp.n_chunks):
+    for c in range(n_chunks):
         lo, hi = int(wl.chunk_rows[c]), int(wl.chunk_rows[c + 1])
         if compact:   # the pool dropped the recompute set: only the other rows of the chunk, in order
             kept = np.setdiff1d(np.arange(lo, hi), wl.sel_idx)
             kc, vc = pinned_bf16(k_cache[kept]), pinned_bf16(v_cache[kept])
             keep_alive.append((kc, vc))
             entries.append(dict(k=kc, v=vc, n_tokens=hi - lo, old_pos_start=int(wl.chunk_old_start[c]),
-                                new_pos_start=int(wl.chunk_new_start[c]), location=2))
+                                new_pos_start=int(wl.chunk_new_start[c]), location=2, raw_keys=int(raw)))
             continue
         on_device = mixed and c % 3 == 1
         entries.append(dict(k=(k_dev if on_device else k_pool)[lo:hi], v=(v_dev if on_device else v_pool)[lo:hi],
                             n_tokens=hi - lo, old_pos_start=int(wl.chunk_old_start[c]),
                             new_pos_start=int(wl.chunk_new_start[c]),
-                            location=0 if on_device else (1 if (pinned or mixed) else 0)))
+                            location=0 if on_device else (1 if (pinned or mixed) else 0), raw_keys=int(raw)))
     chunks = B.make_chunks(entries)
     ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
     if state:      # room for the running (O, max, sum): attention follows the chunk groups key range by key range
@@ -261,23 +302,25 @@ def _run_layer(wl, pinned=False, poison=True, in_place=False, pageable=False, co
     out = torch.full((n_sel, sh.n_q_heads, sh.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
-    say(f"layer {sp.name} n_ctx={n_ctx} n_sel={n_sel} pinned={pinned} in_place={in_place} ws={ws_bytes}")
-    B.ct_partial_prefill_layer(cfg, chunks, sp.n_chunks, hidden, rows, sel, n_sel, sp.ratio_pct / 100.0, wqkv, None,
+    say(f"layer {sp.name} n_ctx={n_ctx} n_sel={n_sel} chunks={n_chunks} pinned={pinned} pageable={pageable} "
+        f"compact={compact} mixed={mixed} in_place={in_place} raw={raw} state={state} ws={ws_bytes}")
+    B.ct_partial_prefill_layer(cfg, chunks, n_chunks, hidden, rows, sel, n_sel, sp.ratio_pct / 100.0, wqkv, None,
                                k_buf, v_buf, out, ws, ws_bytes, compute, copy)
     torch.cuda.synchronize()
     return out, k_buf, v_buf
 
 
-def _oracle_layer(wl, rows=None):
+def _oracle_layer(wl, rows=None, raw=False):
     sh = wl.spec.shape
     hid = W.bf16_bits_to_f64(wl.hidden if wl.hidden_rows is None else wl.hidden[wl.hidden_rows])
+    old_pos = np.zeros_like(wl.old_pos) if raw else wl.old_pos     # a raw cache: keys never rotated
     return O.partial_prefill_layer(hid, W.bf16_bits_to_f64(wl.wqkv), None, W.bf16_bits_to_f64(wl.k_cache),
-                                   W.bf16_bits_to_f64(wl.v_cache), wl.old_pos, wl.new_pos, wl.sel_idx,
+                                   W.bf16_bits_to_f64(wl.v_cache), old_pos, wl.new_pos, wl.sel_idx,
                                    sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta, sh.rope_style, rows=rows)
 
 
-def _check_layer(wl, out, k_buf, v_buf, rows=None):
-    want, _, k_want, v_want = _oracle_layer(wl, rows=rows)
+def _check_layer(wl, out, k_buf, v_buf, rows=None, raw=False):
+    want, _, k_want, v_want = _oracle_layer(wl, rows=rows, raw=raw)
     got = f64_of(out)
     assert np.isfinite(got).all(), "a stale or unwritten row leaked into the attention output"
     assert_close(got if rows is None else got[rows], want, f"{wl.spec.name} attention output")
@@ -296,6 +339,59 @@ def test_layer_config1(mode):
     out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place",
                              pageable=mode == "pageable", compact=mode == "compact", state=state)
     _check_layer(wl, out, kb, vb)
+
+
+@pytest.mark.parametrize("mode", ["pool", "in_place", "pinned", "pinned_state", "pageable", "compact", "mixed"])
+def test_layer_config1_raw_key_cache(mode):
+    """The paper's own cache scheme (Eq. 8): the pool holds keys as they were before RoPE, and
+    token t of a chunk is rotated by its global position new_pos_start + t - for a compact pool
+    by the position of the row it stands for, not by its place in the pool."""
+    wl = W.make_workload(W.spec(1))
+    state = mode.endswith("_state")
+    mode = mode.replace("_state", "")
+    out, kb, vb = _run_layer(wl, pinned=mode == "pinned", in_place=mode == "in_place", poison=mode != "in_place",
+                             pageable=mode == "pageable", compact=mode == "compact", mixed=mode == "mixed", state=state,
+                             raw=True)
+    _check_layer(wl, out, kb, vb, raw=True)
+
+
+def _ragged_workload(shape, lengths, ratio_pct, seed):
+    """A context of chunks of unequal lengths, none a multiple of the attention kernel's 64-key tile."""
+    n_ctx = int(sum(lengths))
+    wl = W.make_workload(W.custom_spec(f"ragged-{n_ctx}", shape, 1, n_ctx, ratio_pct, seed=seed))
+    starts = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    wl.chunk_rows = starts
+    wl.chunk_new_start = starts[:-1].copy()
+    wl.chunk_old_start = np.zeros(len(lengths), dtype=np.int32)
+    wl.old_pos = np.concatenate([np.arange(n, dtype=np.int32) for n in lengths])   # every chunk cached at 0..len-1
+    return wl
+
+
+@pytest.mark.parametrize("mode", ["pool", "pinned", "pinned_state", "compact_state", "pageable"])
+def test_layer_ragged_chunks_tiny(mode):
+    """Chunks of 200 / 333 / 491 / ... tokens: with room for the attention state the launches end at
+    chunk-group boundaries inside a 64-key tile, while the rows behind the boundary are still NaN."""
+    wl = _ragged_workload(W.TINY, [200, 333, 491, 157, 400, 419], 15, seed=41)
+    state = mode.endswith("_state")
+    mode = mode.replace("_state", "")
+    out, kb, vb = _run_layer(wl, pinned=mode == "pinned", pageable=mode == "pageable", compact=mode == "compact", state=state)
+    _check_layer(wl, out, kb, vb)
+
+
+@pytest.mark.parametrize("state", [False, True])
+def test_layer_ragged_chunks_attention_follows_the_groups(state):
+    """Llama head layout, 13 chunks of odd lengths in pinned host memory, r = 50 %: enough (tile,
+    head) pairs (400) for one attention launch per group of chunks, tile by tile or - with the state -
+    key range by key range; group ends fall inside 64-key tiles, and the buffers start as NaN."""
+    lengths = [491, 333, 777, 200, 613, 509, 387, 451, 702, 299, 555, 641, 442]
+    assert sum(lengths) == 6400
+    wl = _ragged_workload(W.LLAMA3_8B, lengths, 50, seed=42)
+    out, kb, vb = _run_layer(wl, pinned=True, state=state)
+    ends = np.cumsum(lengths)
+    near = np.flatnonzero(np.min(np.abs(wl.sel_idx[:, None] - ends[None, :]), axis=1) < 40)   # rows at the chunk boundaries
+    rows = np.unique(np.concatenate([W.sample_rows(wl.spec.n_sel, 96, seed=42), near[::3][:64]]))
+    _check_layer(wl, out, kb, vb, rows=rows)
+    assert torch.isfinite(out.float()).all()
 
 
 @pytest.mark.parametrize("ratio", [100, 0])

@@ -98,6 +98,37 @@ def test_linear_with_workspace_splits_the_last_round(n, k_len, n_out, res):
     assert torch.equal(small, plain)
 
 
+@pytest.mark.parametrize("n,k_len,n_out,n_cu,res", [
+    (4915, 14336, 4096, 224, True),     # the stack's FFN down projection beside a transfer: 224 whole tiles + 96 x 2 parts
+    (4915, 4096, 4096, 224, True),      # its output projection planned for 224 units
+    (4915, 14336, 4096, 216, True),     # 216 + 104 x 2
+    (1300, 8192, 4096, 100, False),     # 96 tiles on 100 units: one round, nothing to split
+    (2100, 8192, 4096, 100, True)])     # 144 tiles on 100 units: 100 whole + 44 x 2
+def test_linear_planned_for_fewer_compute_units(n, k_len, n_out, n_cu, res):
+    """ct_linear_ws_cus: the launch plan the stack uses for the GEMMs that run beside the stream-in
+    kernel (whole rounds over n_cu compute units, the rest split along the reduction)."""
+    rng = np.random.default_rng([35, n, k_len, n_cu])
+    x, w = _bits(rng, (n, k_len)), _bits(rng, (n_out, k_len), 1.0 / math.sqrt(k_len))
+    r = _bits(rng, (n, n_out)) if res else None
+    ws_bytes = B.ct_linear_workspace_bytes(n, k_len, n_out)
+    say(f"linear planned for {n_cu} compute units n={n} k={k_len} out={n_out} workspace={ws_bytes >> 20} MiB")
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    out = torch.zeros((n, n_out), dtype=torch.bfloat16, device="cuda")
+    B.ct_linear_ws_cus(xd, n, k_len, wd, n_out, None if r is None else dev_bf16(r), out, ws, ws_bytes, n_cu)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(64), np.arange(n - 300, n), rng.integers(0, n, 256)]))
+    want = W.bf16_bits_to_f64(x[rows]) @ W.bf16_bits_to_f64(w).T
+    if res:
+        want = want + W.bf16_bits_to_f64(r[rows])
+    assert_close(f64_of(out)[rows], want, f"linear planned for {n_cu} units")
+    plain = torch.zeros_like(out)       # every element against the unsplit kernel: one bf16 step at most
+    B.ct_linear(xd, n, k_len, wd, n_out, None if r is None else dev_bf16(r), plain)
+    torch.cuda.synchronize()
+    d = (out.float() - plain.float()).abs()
+    assert float((d / plain.float().abs().clamp_min(0.25)).max()) <= 2.0 ** -7
+
+
 @pytest.mark.parametrize("n,k_len,n_out", [(257, 512, 1408), (129, 4096, 14336), (7, 64, 64)])
 def test_swiglu(n, k_len, n_out):
     rng = np.random.default_rng([33, n, k_len, n_out])
@@ -109,7 +140,7 @@ def test_swiglu(n, k_len, n_out):
     torch.cuda.synchronize()
     xf = W.bf16_bits_to_f64(x)
     want = O.silu(xf @ W.bf16_bits_to_f64(wg).T) * (xf @ W.bf16_bits_to_f64(wu).T)
-    assert_close(f64_of(out), want, "swiglu", ulp_slack=2.0 ** -8)   # products of two N(0,1) projections reach 16
+    assert_close(f64_of(out), want, "swiglu", rounding_slack_from=4.0)   # products of two N(0,1) projections reach 16
 
 
 # ------------------------------------------------------------------------------ the stack
@@ -155,7 +186,8 @@ def _run_stack(sw, hidden0_bits, layer_range=None, pinned=True):
 @pytest.mark.parametrize("pinned", [True, False])
 @pytest.mark.parametrize("ratio", [15, 100])
 def test_small_stack_end_to_end(pinned, ratio):
-    """4 layers, unforced: bf16 rounding compounds through the layers, so the bound is looser."""
+    """4 layers, unforced: bf16 rounding compounds through the layers, so the bound is looser than
+    for one layer (observed: max-abs 5.6e-2, worst row 7.9e-3 relative)."""
     sh = W.LayerShape(512, 8, 2, 64, 1.0e4)
     sp = W.custom_spec(f"stack-small-r{ratio}", sh, 4, 512, ratio, seed=77)
     sw = W.make_stack_workload(sp, n_layers=4, ffn_dim=1408)
@@ -163,7 +195,7 @@ def test_small_stack_end_to_end(pinned, ratio):
     f = _layers_f64(sw)
     want = O.partial_prefill_stack(W.bf16_bits_to_f64(sw.hidden0), f, sw.old_pos, sw.new_pos, sw.sel_idx,
                                    sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta, sw.rms_eps)
-    assert_close(f64_of(h), want, "4-layer stack output", max_abs=1e-1, rel_l2=2e-2, ulp_slack=2.0 ** -7)   # unforced: rounding compounds over 4 layers
+    assert_close(f64_of(h), want, "4-layer stack output", max_abs=8e-2, rel_l2=1.5e-2, rounding_slack_from=4.0)
 
 
 def test_llama_shaped_layers_teacher_forced():
@@ -180,3 +212,71 @@ def test_llama_shaped_layers_teacher_forced():
                                          sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.rope_theta, sw.rms_eps)
         assert_close(f64_of(h_out), want, f"layer {l} output (teacher forced)", ulp_slack=2.0 ** -8)
         h_in = bits_of(h_out)
+
+
+def test_ratio_search_on_measured_stack_latency():
+    """Alg. 1 with its real objective (Eq. 12): EvalTTFT is the measured latency of a shrunk stack
+    (4 layers, 16384-token context in pinned host memory) at the probed ratio.  Every probe lies
+    inside the bracket, their number is what the bracket and eps allow, and the latency at r* is
+    within the measurement's spread of the best point of a coarse grid scan of the same function."""
+    import time
+    sh = W.LayerShape(1024, 8, 2, 128, 5.0e5)
+    sp = W.custom_spec("stack-tune", sh, 16, 1024, 15, seed=79)
+    n_layers, ffn, N = 4, 2816, sp.n_ctx
+    sw = W.make_stack_workload(sp, n_layers=n_layers, ffn_dim=ffn)
+    cfg = B.cfg_from_shape(sh)
+    keep, entries = [], []
+    for lw in sw.layers:
+        d = {k: dev_bf16(lw[k]) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")}
+        kp, vp = pinned_bf16(lw["k_cache"]), pinned_bf16(lw["v_cache"])
+        ch = B.make_chunks([dict(k=kp[c * 1024:(c + 1) * 1024], v=vp[c * 1024:(c + 1) * 1024], n_tokens=1024,
+                                 old_pos_start=0, new_pos_start=c * 1024, location=1) for c in range(16)])
+        keep.append((kp, vp, ch))
+        d["chunks"] = ch
+        entries.append(d)
+    layers = B.make_layers(entries)
+    k_bufs = torch.zeros((2, N, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_bufs = torch.zeros_like(k_bufs)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    rng = np.random.default_rng(79)
+
+    def latency(r):
+        n_sel = max(1, int(math.floor(r * N + 1e-9)))
+        sel = dev_i32(W.select_indices(sp, n_sel))
+        h0 = dev_bf16(W.f32_to_bf16_bits(rng.standard_normal((n_sel, sh.hidden)).astype(np.float32)))
+        h = torch.empty_like(h0)
+        ws_bytes = B.ct_stack_workspace_bytes(cfg, ffn, N, n_sel)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        times = []
+        for it in range(6):
+            h.copy_(h0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.ct_partial_prefill_stack(cfg, ffn, sw.rms_eps, layers, n_layers, 16, h, sel, n_sel, r, k_bufs, v_bufs, ws,
+                                       ws_bytes, s1, s2)
+            torch.cuda.synchronize()
+            if it:
+                times.append(time.perf_counter() - t0)
+        assert torch.isfinite(h.float()).all()
+        return float(np.median(times)) * 1e3
+
+    r_min, r_max, eps = 0.02, 0.6, 0.02
+    say(f"ratio search over measured latency, shrunk stack: {n_layers} layers, n_ctx={N}")
+    grid = np.linspace(r_min, r_max, 13)
+    scan = [latency(r) for r in grid]
+    seen = []
+
+    def ttft(r):
+        seen.append((r, latency(r)))
+        return seen[-1][1]
+    r0 = float(grid[int(np.argmin(scan))]) * 0.8 + 0.2 * r_min          # a prior near, not at, the scan's best point
+    r_star, n_evals = B.ct_ratio_search(ttft, r0, r_min, r_max, eps)
+    print(f"[tune] scan {[f'{r:.3f}:{t:.3f}' for r, t in zip(grid, scan)]}; r0 {r0:.3f} -> r* {r_star:.3f} after {n_evals} "
+          f"evaluations; probes {[f'{r:.3f}:{t:.3f}' for r, t in seen]}", flush=True)
+    assert n_evals == len(seen) and 2 <= n_evals <= 2 + math.ceil(math.log(eps / (r_max - r_min)) / math.log(0.618)) + 2
+    assert all(r_min < r < r_max for r, _ in seen) and r_min <= r_star <= r_max
+    # same probes as the oracle's search over the recorded values (the search itself is host code)
+    table = dict(seen)
+    want, probes = O.ratio_search(lambda r: table[min(table, key=lambda x: abs(x - r))], r0, r_min, r_max, eps)
+    assert np.allclose(probes, [r for r, _ in seen], atol=1e-12) and abs(want - r_star) <= 1e-12
+    assert latency(r_star) <= 1.15 * min(scan) + 0.05
