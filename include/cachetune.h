@@ -148,6 +148,20 @@ ct_status ct_selected_attention(const ct_layer_cfg* cfg, const void* q_sel, cons
                                 int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel, void* out, float* lse,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* ct_selected_attention for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and kernels; the scratch lives in a device array inside the library (one copy per GPU,
+ * ct_static_scratch_bytes() = 64 MiB, held until the process ends) instead of a workspace.  The
+ * call allocates nothing.  A problem whose scratch exceeds the array is rejected with
+ * CT_ERR_WORKSPACE before anything is launched.  Every call on a GPU uses that GPU's one array:
+ * calls that overlap in time on the same GPU (two streams, two threads) race; calls ordered on
+ * one stream do not.  The array keeps the last call's contents; the call clears what it needs
+ * cleared itself. */
+ct_status ct_selected_attention_static(const ct_layer_cfg* cfg, const void* q_sel, const void* k_buf,
+                                       const void* v_buf, int32_t n_ctx, const int32_t* sel_idx, int32_t n_sel,
+                                       void* out, float* lse, void* stream);
+size_t ct_static_scratch_bytes(void);
+
 /* One fusion-layer step of the online pipeline (Sec. 4.2; its cost model is Eq. 9):
  *   compute stream: device chunks are read from chunk.k / chunk.v, rotated and written to
  *                   the buffers (all but the rows listed in sel_idx, which are recomputed); a

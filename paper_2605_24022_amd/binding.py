@@ -22,6 +22,7 @@ KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 
 
 EXPORTS = [
     "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_keys_skip", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
+    "ct_selected_attention_static", "ct_static_scratch_bytes",
     "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_attention_state_bytes", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
     "ct_rmsnorm", "ct_linear", "ct_linear_ws", "ct_linear_ws_cus", "ct_linear_workspace_bytes", "ct_swiglu", "ct_partial_prefill_stack", "ct_partial_prefill_stack_tap", "ct_stack_workspace_bytes",
@@ -77,6 +78,10 @@ def load() -> ctypes.CDLL:
     lib.ct_rerope_chunk.argtypes = [cfgp, P, P, P, P, c_int32, c_int32, c_int32, c_int32, P]
     lib.ct_scatter_kv.argtypes = [cfgp, P, P, c_int32, P, P, P, c_int32, P]
     lib.ct_selected_attention.argtypes = [cfgp, P, P, P, c_int32, P, c_int32, P, P, P, c_size_t, P]
+    lib.ct_selected_attention_static.argtypes = [cfgp, P, P, P, c_int32, P, c_int32, P, P, P]
+    lib.ct_selected_attention_static.restype = c_int32
+    lib.ct_static_scratch_bytes.argtypes = []
+    lib.ct_static_scratch_bytes.restype = c_size_t
     lib.ct_partial_prefill_layer.argtypes = [cfgp, POINTER(Chunk), c_int32, P, P, P, c_int32, c_double, P, P,
                                              P, P, P, P, c_size_t, P, P]
     lib.ct_rmsnorm.argtypes = [P, P, c_float, c_int32, c_int32, P, P]
@@ -216,6 +221,15 @@ def ct_selected_attention(cfg, q_sel, k_buf, v_buf, n_ctx, sel_idx, n_sel, out, 
     _check(load().ct_selected_attention(byref(cfg), _ptr(q_sel), _ptr(k_buf), _ptr(v_buf), n_ctx, _ptr(sel_idx),
                                         n_sel, _ptr(out), _ptr(lse), _ptr(workspace), workspace_bytes,
                                         _stream(stream)))
+
+
+def ct_selected_attention_static(cfg, q_sel, k_buf, v_buf, n_ctx, sel_idx, n_sel, out, lse, stream=None) -> None:
+    _check(load().ct_selected_attention_static(byref(cfg), _ptr(q_sel), _ptr(k_buf), _ptr(v_buf), n_ctx, _ptr(sel_idx),
+                                               n_sel, _ptr(out), _ptr(lse), _stream(stream)))
+
+
+def ct_static_scratch_bytes() -> int:
+    return int(load().ct_static_scratch_bytes())
 
 
 def make_chunks(entries: Sequence[dict]):

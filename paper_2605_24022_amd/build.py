@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libcachetune.so")
-SOURCES = ["ct_api.hip", "ct_rerope_scatter.hip", "ct_gemm.hip", "ct_stack.hip", "ct_attention.hip", "ct_schedule.hip", "ct_frequency.hip"]
+SOURCES = ["ct_api.hip", "ct_rerope_scatter.hip", "ct_gemm.hip", "ct_stack.hip", "ct_attention.hip", "ct_schedule.hip", "ct_frequency.hip", "ct_noalloc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

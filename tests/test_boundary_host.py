@@ -103,6 +103,20 @@ def test_rerope_skip_and_planned_linear_validation():
     B.ct_linear_ws_cus(None, 0, 512, None, 512, None, None, None, 0, 224)
 
 
+def test_static_scratch_entry_point_rejects_on_the_host():
+    """ct_selected_attention_static: the same argument checks as ct_selected_attention, and a clear
+    error - before any HIP call - for a problem whose scratch does not fit the library's array."""
+    c = _cfg()
+    assert B.ct_static_scratch_bytes() == 64 << 20
+    assert _status(B.ct_selected_attention_static, c, None, FAKE, FAKE, 64, FAKE, 4, FAKE, None) == B.CT_ERR_NULL
+    assert _status(B.ct_selected_attention_static, c, FAKE, FAKE, FAKE, 0, FAKE, 4, FAKE, None) == B.CT_ERR_SHAPE
+    assert _status(B.ct_selected_attention_static, c, FAKE, FAKE, FAKE, 64, FAKE, 65, FAKE, None) == B.CT_ERR_SHAPE
+    with pytest.raises(B.CacheTuneError) as e:      # 376 (tile, head) pairs split in two: 100 MB of partials
+        B.ct_selected_attention_static(c, FAKE, FAKE, FAKE, 65536, FAKE, 3000, FAKE, None)
+    assert e.value.status == B.CT_ERR_WORKSPACE and "static" in e.value.message
+    B.ct_selected_attention_static(c, None, None, None, 64, None, 0, None, None)     # empty work is legal
+
+
 def test_attention_workspace_checks():
     c = _cfg()
     need = B.ct_workspace_bytes(c, 32768, 1638)   # few tiles -> split keys -> partials in the workspace
