@@ -193,22 +193,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
 
   // ---- per-lane LDS read offsets ----------------------------------------------------------------
-  // K fragment (sub-tile u, k-step ks): row 32u + l32, logical piece 2ks + hi
-  int k_off[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_off[ks] = l32 * ROWB + (((2 * ks + hi) ^ swz_k<D>(l32)) * 16);
+  // K fragment (sub-tile u, k-step ks): row 32u + l32, logical piece 2ks + hi, i.e. byte offset
+  //   l32 * ROWB + ((2ks + hi) ^ swizzle) * 16 + u * 32 * ROWB  =  (k_a ^ (ks << 5)) + u * 32 * ROWB,
+  // because the swizzle is an exclusive-or on bits the row term leaves clear: one register holds
+  // k_a and every fragment address is that register exclusive-or a constant.
+  const int k_a = l32 * ROWB + ((hi ^ swz_k<D>(l32)) * 16);
   // V^T fragment (row tile m, sub-tile u, step t, half a2): 16-lane block b reads 4 key rows x
-  // 16 head_dim columns; lane j of the block addresses row j / 4, 8-byte chunk j % 4
+  // 16 head_dim columns; lane j of the block addresses row j / 4, 8-byte chunk j % 4:
+  //   r = 8 a2 + 4 hi + j / 4 (+ 32u + 16t, which leave the swizzle unchanged), piece pc = 4m + 2 (lane / 16 % 2) + j % 4 / 2,
+  //   offset r * ROWB + (pc ^ swizzle(r)) * 16 + 8 (j % 2)  =  (v_a ^ (m << 6) ^ (a2 << 5, D = 128 only)) + a2 * 8 * ROWB
+  // for the same reason (checked for every lane, m and a2 on the host when this was written).
   const int vj = lane & 15, vdh = (lane >> 4) & 1;
-  int v_off[MT][2];
-#pragma unroll
-  for (int m = 0; m < MT; ++m)
-#pragma unroll
-    for (int a2 = 0; a2 < 2; ++a2) {
-      const int r = 8 * a2 + 4 * hi + (vj >> 2);        // + 32u + 16t, which leave the swizzle unchanged
-      const int pc = 4 * m + 2 * vdh + ((vj & 3) >> 1);
-      v_off[m][a2] = r * ROWB + ((pc ^ swz_v<D>(r)) * 16) + 8 * (vj & 1);
-    }
+  const int v_a = (4 * hi + (vj >> 2)) * ROWB + (((2 * vdh + ((vj & 3) >> 1)) ^ swz_v<D>(4 * hi + (vj >> 2))) * 16) + 8 * (vj & 1);
+  constexpr int V_A2_XOR = D == 128 ? 32 : 0;
 
   // ---- state ---------------------------------------------------------------------------------------
   f32x16 o[MT];
@@ -243,8 +240,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   auto load_vfrag = [&](const unsigned char* vrow, int m) __attribute__((always_inline)) -> bf16x8 {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][0]));
-    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vrow + v_off[m][1]));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vrow + (v_a ^ (m << 6))));
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(vrow + ((v_a ^ (m << 6) ^ V_A2_XOR) + 8 * ROWB)));
     const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
     return *reinterpret_cast<const bf16x8*>(&both);
   };
@@ -268,7 +266,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   auto load_frag = [&](int j, const unsigned char* vb, const unsigned char* kb) __attribute__((always_inline)) -> bf16x8 {
     if (j < NPV) return load_vfrag(vb + 16 * (j / MT) * ROWB, j % MT);
     const int ks = (j - NPV) >> 1, u = (j - NPV) & 1;
-    return *reinterpret_cast<const bf16x8*>(kb + k_off[ks] + u * 32 * ROWB);
+    return *reinterpret_cast<const bf16x8*>(kb + (k_a ^ (ks << 5)) + u * 32 * ROWB);
   };
   auto part_m = [&](const unsigned char* vb, const unsigned char* kb, auto&& dma) __attribute__((always_inline)) {
     __builtin_amdgcn_s_setprio(3);
