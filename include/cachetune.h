@@ -223,6 +223,19 @@ size_t ct_workspace_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel)
  * 0 for an invalid configuration or n_sel = 0. */
 size_t ct_attention_state_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t n_sel);
 
+/* Which rows of k_buf / v_buf one attention launch of a host-pool layer reads (Sec. 4.2: the
+ * attention follows the chunk groups while later groups are still on the host link, so a launch over
+ * the keys [key_after, key_upto) must not touch a row from key_upto on).  Replays, on the host, the
+ * tile loads of the launch that ct_partial_prefill_layer issues for that key range - with_state != 0:
+ * the launch with the attention state, every unfinished tile through the range; 0: the tile-by-tile
+ * launch, tiles whose last visible key lies in the range - with the index arithmetic the kernel uses.
+ * sel_idx_host: host memory, n_sel strictly ascending rows.  first_row / last_row receive the lowest
+ * and highest row read (-1 and -1 when the launch has no work).  Host function, no GPU call.
+ * Errors: CT_ERR_NULL, CT_ERR_SHAPE (sizes, key range), CT_ERR_INDEX (indices). */
+ct_status ct_attention_rows_read(const ct_layer_cfg* cfg, const int32_t* sel_idx_host, int32_t n_sel, int32_t n_ctx,
+                                 int32_t key_after, int32_t key_upto, int32_t with_state, int32_t* first_row,
+                                 int32_t* last_row);
+
 /* ---- The rest of a transformer layer on the selected rows, and the multi-layer partial prefill.
  * After the check layer every layer of the model runs on the selected tokens only (Sec. 4.2,
  * fusion layers); the non-selected tokens contribute their cached K/V and nothing else. ---- */

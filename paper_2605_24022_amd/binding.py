@@ -23,7 +23,7 @@ KERNEL_CLASSES = {"qkv": 0, "rerope": 1, "scatter": 2, "attention": 3, "merge": 
 EXPORTS = [
     "ct_qkv_selected", "ct_rerope_keys", "ct_rerope_keys_skip", "ct_rerope_chunk", "ct_scatter_kv", "ct_selected_attention",
     "ct_selected_attention_static", "ct_static_scratch_bytes",
-    "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_attention_state_bytes", "ct_validate_indices", "ct_set_profiling",
+    "ct_partial_prefill_layer", "ct_workspace_bytes", "ct_attention_state_bytes", "ct_attention_rows_read", "ct_validate_indices", "ct_set_profiling",
     "ct_profile_reset", "ct_profile_read", "ct_last_error", "ct_version",
     "ct_rmsnorm", "ct_linear", "ct_linear_ws", "ct_linear_ws_cus", "ct_linear_workspace_bytes", "ct_swiglu", "ct_partial_prefill_stack", "ct_partial_prefill_stack_tap", "ct_stack_workspace_bytes",
     "ct_measure_mfma_rate", "ct_layer_latency_model", "ct_ratio_prior", "ct_ratio_search",
@@ -102,6 +102,8 @@ def load() -> ctypes.CDLL:
     lib.ct_workspace_bytes.restype = c_size_t
     lib.ct_attention_state_bytes.argtypes = [cfgp, c_int32, c_int32]
     lib.ct_attention_state_bytes.restype = c_size_t
+    lib.ct_attention_rows_read.argtypes = [cfgp, P, c_int32, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32),
+                                           POINTER(c_int32)]
     lib.ct_validate_indices.argtypes = [P, c_int32, c_int32]
     lib.ct_set_profiling.argtypes = [c_int32]
     lib.ct_set_profiling.restype = None
@@ -182,6 +184,16 @@ def ct_workspace_bytes(cfg: LayerCfg, n_ctx: int, n_sel: int) -> int:
 
 def ct_attention_state_bytes(cfg: LayerCfg, n_ctx: int, n_sel: int) -> int:
     return int(load().ct_attention_state_bytes(byref(cfg), n_ctx, n_sel))
+
+
+def ct_attention_rows_read(cfg: LayerCfg, host_idx, n_sel: int, n_ctx: int, key_after: int, key_upto: int,
+                           with_state: bool):
+    """host_idx: numpy int32 array.  Returns (first_row, last_row) of the key rows that launch reads."""
+    lo, hi = c_int32(0), c_int32(0)
+    p = None if host_idx is None else host_idx.ctypes.data
+    _check(load().ct_attention_rows_read(byref(cfg), p, n_sel, n_ctx, key_after, key_upto, int(bool(with_state)),
+                                         byref(lo), byref(hi)))
+    return lo.value, hi.value
 
 
 def ct_validate_indices(host_idx, n_sel: int, n_ctx: int) -> None:

@@ -393,6 +393,19 @@ size_t ct_attention_state_bytes(const ct_layer_cfg* cfg, int32_t n_ctx, int32_t 
   return (attention_state_bytes(cfg, n_ctx, n_sel) + 255) & ~(size_t)255;
 }
 
+ct_status ct_attention_rows_read(const ct_layer_cfg* cfg, const int32_t* sel_idx_host, int32_t n_sel, int32_t n_ctx,
+                                 int32_t key_after, int32_t key_upto, int32_t with_state, int32_t* first_row,
+                                 int32_t* last_row) {
+  ct_status st = check_cfg(cfg);
+  if (st != CT_OK) return st;
+  if (!sel_idx_host || !first_row || !last_row) return fail(CT_ERR_NULL, "sel_idx_host, first_row and last_row must be non-NULL");
+  if (n_ctx <= 0 || n_sel <= 0 || n_sel > n_ctx) return fail(CT_ERR_SHAPE, "bad size (n_ctx %d, n_sel %d)", n_ctx, n_sel);
+  if (key_after < 0 || key_upto <= key_after)
+    return fail(CT_ERR_SHAPE, "key range [%d, %d) is empty or negative", key_after, key_upto);
+  if ((st = check_indices_host(sel_idx_host, n_sel, n_ctx)) != CT_OK) return st;
+  return attention_rows_read(cfg, sel_idx_host, n_sel, n_ctx, key_after, key_upto, with_state != 0, first_row, last_row);
+}
+
 ct_status ct_qkv_selected(const ct_layer_cfg* cfg, const void* hidden, const int32_t* hidden_rows,
                           const int32_t* sel_pos, int32_t n_sel, const void* wqkv, const void* bias, void* q_out,
                           void* k_out, void* v_out, void* stream) {

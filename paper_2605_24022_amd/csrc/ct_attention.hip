@@ -56,6 +56,30 @@ struct AttnArgs {
   float scale_log2;   // softmax scale * log2(e)
 };
 
+// The keys one workgroup (tile, key-range split) of a launch works through: [k_lo, k_hi), or nothing.
+// Shared by the kernel and by the host-side check of the rows a launch reads.
+struct ItemRange {
+  int k_lo, k_hi;
+  bool active;
+};
+__host__ __device__ inline ItemRange item_range(int kmax, int split, int split_keys, bool resumable, int key_after,
+                                                int key_upto) {
+  ItemRange r = {0, 0, false};
+  if (kmax <= key_after || (!resumable && kmax > key_upto)) return r;   // another launch's tile
+  r.k_lo = resumable ? key_after : split * split_keys;
+  if (r.k_lo >= kmax) return r;                                          // empty split
+  r.k_hi = resumable ? (key_upto < kmax ? key_upto : kmax)
+                     : (r.k_lo + split_keys < kmax ? r.k_lo + split_keys : kmax);
+  r.active = true;
+  return r;
+}
+// Row of the K (or V) buffer behind row `row_in_tile` of the LDS tile that starts at key k0: rows from
+// k_hi on (the end of the item's key range) are replaced by row k_hi - 1.
+__host__ __device__ inline int tile_load_row(int k0, int row_in_tile, int k_hi) {
+  const int key = k0 + row_in_tile;
+  return key < k_hi - 1 ? key : k_hi - 1;
+}
+
 // v_permlane32_swap exchanges the upper half of the first operand with the lower half of
 // the second: with both operands x, result[0] is (x | partner) and result[1] is
 // (partner | x) over (lanes 0-31 | lanes 32-63), so any commutative combination of the two
@@ -130,10 +154,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int last_tok = min(tok0 + a.TM, a.n_sel) - 1;
   const int kmax = a.sel_idx[last_tok] + 1;              // keys this tile can see
   const bool resumable = a.state != nullptr;
-  if (kmax <= a.key_after || (!resumable && kmax > a.key_upto)) return;  // another launch's tile (uniform for the workgroup)
-  const int k_lo = resumable ? a.key_after : split * a.split_keys;
-  if (k_lo >= kmax) return;                              // empty split (uniform for the workgroup)
-  const int k_hi = resumable ? min(a.key_upto, kmax) : min(k_lo + a.split_keys, kmax);
+  const ItemRange item = item_range(kmax, split, a.split_keys, resumable, a.key_after, a.key_upto);
+  if (!item.active) return;                              // uniform for the workgroup
+  const int k_lo = item.k_lo, k_hi = item.k_hi;
   const int n_kt = (k_hi - k_lo + BN - 1) / BN;
 
   // ---- this lane's query column ------------------------------------------------------------------
@@ -184,7 +207,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // but what stands in those rows may not have been written yet - a later group of chunks still on
   // the host link - and a non-finite bit pattern there would turn 0 * v into NaN in the PV product.
   auto issue_one = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr, int idx) __attribute__((always_inline)) {
-    const int key = min(k0 + ld_row + NWAVES * RPI * idx, k_hi - 1);
+    const int key = tile_load_row(k0, ld_row + NWAVES * RPI * idx, k_hi);
     dma16(base, __umul24(key, kv_row_bytes) + lane_off, stage_addr + (NWAVES * idx + wave) * 1024);
   };
   auto issue_rows = [&](const uint16_t* base, uint32_t lane_off, int k0, uint32_t stage_addr) __attribute__((always_inline)) {
@@ -533,6 +556,33 @@ ct_status launch_attention(const ct_layer_cfg* cfg, const void* q_sel, const voi
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "attention merge kernel launch");
   }
+  return CT_OK;
+}
+
+// Host-side replay of the key rows one launch reads (same item and row functions as the kernel, same
+// tile loads: the prologue's K(0), K(1), V(0) and stand-in, then K(i + 2) and V(i + 1) in period i).
+ct_status attention_rows_read(const ct_layer_cfg* cfg, const int32_t* sel_idx_host, int32_t n_sel, int32_t n_ctx,
+                              int32_t key_after, int32_t key_upto, bool resumable, int32_t* first_row,
+                              int32_t* last_row) {
+  const AttnPlan p = plan_attention(cfg, n_ctx, n_sel);
+  int lo = 0x7fffffff, hi = -1;
+  for (int tile = 0; tile < p.n_tiles; ++tile) {
+    const int last_tok = (tile * p.tile_tokens + p.tile_tokens < n_sel ? tile * p.tile_tokens + p.tile_tokens : n_sel) - 1;
+    const int kmax = sel_idx_host[last_tok] + 1;
+    for (int split = 0; split < p.n_splits; ++split) {
+      const ItemRange it = item_range(kmax, split, p.split_keys, resumable, key_after, key_upto);
+      if (!it.active) continue;
+      const int n_kt = (it.k_hi - it.k_lo + BN - 1) / BN;
+      for (int t = 0; t <= n_kt + 2; ++t)          // tiles 0 .. n_kt + 2 of the item are loaded
+        for (int r = 0; r < BN; r += BN - 1) {     // first and last row of a tile bound the others
+          const int row = tile_load_row(it.k_lo + t * BN, r, it.k_hi);
+          lo = row < lo ? row : lo;
+          hi = row > hi ? row : hi;
+        }
+    }
+  }
+  *first_row = hi < 0 ? -1 : lo;
+  *last_row = hi;
   return CT_OK;
 }
 

@@ -68,6 +68,10 @@ struct AttnPlan {
   size_t ws_bytes;   // workspace bytes needed
 };
 AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel);
+// Lowest and highest key row the attention launch over keys [key_after, key_upto) reads (host replay).
+ct_status attention_rows_read(const ct_layer_cfg* cfg, const int32_t* sel_idx_host, int32_t n_sel, int32_t n_ctx,
+                              int32_t key_after, int32_t key_upto, bool resumable, int32_t* first_row,
+                              int32_t* last_row);
 // Scratch bytes launch_attention needs behind its `workspace` pointer for this problem size.
 size_t attention_scratch_bytes(const ct_layer_cfg* cfg, int n_ctx, int n_sel);
 

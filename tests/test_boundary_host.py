@@ -117,6 +117,40 @@ def test_static_scratch_entry_point_rejects_on_the_host():
     B.ct_selected_attention_static(c, None, None, None, 64, None, 0, None, None)     # empty work is legal
 
 
+def test_attention_launches_over_ragged_chunk_groups_stay_inside_their_key_range():
+    """Sec. 4.2, chunk-wise overlap: the attention launch that follows a group of host chunks may read
+    no key row of a later group (it may still be on the host link).  The host replay of the kernel's
+    tile loads says which rows a launch reads; group ends that are no multiple of the 64-key tile are
+    the case that matters.  Also: every row a launch needs is read, and argument errors are reported."""
+    c = _cfg()
+    rng = np.random.default_rng(7)
+    n_ctx = 200 + 333 + 491 + 1000
+    ends = [200, 533, 1024, n_ctx]                      # ragged group ends
+    for n_sel in (1, 37, 300, n_ctx):
+        sel = np.sort(rng.choice(n_ctx, n_sel, replace=False)).astype(np.int32)
+        for with_state in (False, True):
+            seen = 0
+            for upto in ends:
+                lo, hi = B.ct_attention_rows_read(c, sel, n_sel, n_ctx, seen, upto, with_state)
+                # tiles of 256 / G = 64 selected rows; the last row of a tile decides what the tile sees
+                lasts = np.array([sel[min(t + 64, n_sel) - 1] for t in range(0, n_sel, 64)])
+                if with_state:
+                    active = lasts >= seen                  # every tile that sees keys past `seen`
+                    want_hi = min(upto, lasts[active].max() + 1) - 1 if active.any() else -1
+                    want_lo = seen if active.any() else -1
+                else:
+                    active = (lasts >= seen) & (lasts < upto)
+                    want_hi = lasts[active].max() if active.any() else -1
+                    want_lo = 0 if active.any() else -1
+                assert (lo, hi) == (want_lo, want_hi), (n_sel, with_state, seen, upto)
+                assert hi < upto
+                seen = upto
+    sel = np.arange(8, dtype=np.int32)
+    assert _status(B.ct_attention_rows_read, c, None, 8, 64, 0, 64, False) == B.CT_ERR_NULL
+    assert _status(B.ct_attention_rows_read, c, sel, 8, 64, 10, 10, False) == B.CT_ERR_SHAPE
+    assert _status(B.ct_attention_rows_read, c, sel[::-1].copy(), 8, 64, 0, 64, False) == B.CT_ERR_INDEX
+
+
 def test_attention_workspace_checks():
     c = _cfg()
     need = B.ct_workspace_bytes(c, 32768, 1638)   # few tiles -> split keys -> partials in the workspace
