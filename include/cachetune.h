@@ -363,8 +363,11 @@ ct_status ct_ratio_search(ct_ttft_fn eval, void* user, double r0, double r_min, 
  *               b * batch_stride (batch_stride >= n_tokens * row_elems)
  *   scores      device fp32 [n_batch, n_tokens]
  *   workspace   at least ct_frequency_workspace_bytes() bytes of device memory
- * n_tokens must be of the form 2^a 3^b 5^c and at most 4096 (the transform of a strip of columns
- * is done inside one compute unit's LDS); row_elems even.  CT_ERR_UNSUPPORTED otherwise. */
+ * n_tokens must be of the form 2^a 3^b 5^c; row_elems even.  Up to 4096 tokens the transform of a
+ * strip of columns is done inside one compute unit's LDS; longer sequences (below 2^24 tokens, with
+ * a divisor pair N1 N2 = n_tokens, both at most 4096) are transformed in two factors through one
+ * complex fp32 copy of a tensor in the workspace (n_tokens * row_elems * 4 bytes; the workspace
+ * must then be 256-byte aligned).  CT_ERR_UNSUPPORTED otherwise. */
 ct_status ct_frequency_scores(const void* k, const void* v, int32_t n_batch, int64_t batch_stride, int32_t n_tokens,
                               int32_t row_elems, double alpha, float* scores, void* workspace, size_t workspace_bytes,
                               void* stream);

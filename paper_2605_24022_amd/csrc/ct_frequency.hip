@@ -13,6 +13,15 @@
 // accumulated over the strips a workgroup owns; a second small kernel adds the workgroups'
 // partial sums in a fixed order, so the scores are reproducible bit for bit.
 //
+// Sequences longer than kFreqMaxTokens do not fit one workgroup's LDS: their transform is split as
+// N = N1 N2 (token n = n1 N2 + n2, bin k = k1 + N1 k2) into length-N1 transforms over n1, a twiddle
+// exp(-+2 pi i n2 k1 / N), and length-N2 transforms over n2, each done in LDS by the same passes,
+// with one complex fp32 array of N x (row_elems / 2) per tensor in HBM between them:
+//   A  (n2, strip):  x[n1 N2 + n2] -> FFT over n1 -> * twiddle -> Y[k1 N2 + n2]
+//   B  (k1, strip):  Y[k1 N2 + .]  -> FFT over n2 -> mask bins k1 + N1 k2 -> inverse FFT over k2
+//                    -> * conj twiddle -> Z[k1 N2 + n2]        (in place, contiguous rows)
+//   C  (n2, strip):  Z[. N2 + n2]  -> inverse FFT over k1 -> squares summed per token.
+//
 // TopK (Eq. 7).  One workgroup per sequence: a 4 x 8-bit radix select over the order-preserving
 // integer image of the scores finds the threshold value and how many of the tokens that tie with
 // it still fit (lower index first); an ordered sweep then writes the chosen indices ascending.
@@ -343,6 +352,114 @@ __global__ __launch_bounds__(kFreqThreads) void freq_energy_kernel(const uint16_
   }
 }
 
+// ---- sequences beyond kFreqMaxTokens: N = N1 N2 through HBM -----------------------------------
+constexpr int kFreqLongElems = 8192;   // complex values per workgroup in the long path (8 per thread)
+
+__device__ __forceinline__ void build_twiddles(float2* tw, int n) {
+  for (int t = threadIdx.x; t < (n + 1) / 2; t += kFreqThreads) {
+    float s, c;
+    sincospif(-2.f * ((float)t / (float)n), &s, &c);
+    tw[t] = make_float2(c, s);
+  }
+}
+// exp(sgn 2 pi i a b / n) for a b < 2^48, n < 2^24: the product is reduced exactly before it is rounded
+__device__ __forceinline__ float2 long_twiddle(int a, int b, int n, float sgn) {
+  const int t = (int)(((int64_t)a * b) % n);
+  float s, c;
+  sincospif(2.f * ((float)t / (float)n), &s, &c);
+  return make_float2(c, sgn * s);
+}
+
+// A: one workgroup = one n2 and one strip of 2^lg complex columns (pairs of real columns).
+__global__ __launch_bounds__(kFreqThreads) void freq_long_a_kernel(const uint16_t* __restrict__ src, int32_t width,
+                                                                   FftPlan p1, int32_t n, int32_t n2_len,
+                                                                   float2* __restrict__ scratch) {
+  extern __shared__ float2 lds[];
+  int n1 = p1.n, lg = p1.lg_cp;
+  const int cp = 1 << lg;
+  float2* data = lds;
+  float2* tw = lds + ((n1 + (n1 >> 4) + 1) << lg);
+  const int strips = width >> lg;
+  const int strip = blockIdx.x % strips, n2 = blockIdx.x / strips;
+  build_twiddles(tw, n1);
+  const uint32_t* base = reinterpret_cast<const uint32_t*>(src) + (int64_t)strip * cp;
+  for (int e = threadIdx.x; e < (n1 << lg); e += kFreqThreads) {
+    const int row = e >> lg, c = e & (cp - 1);
+    const uint32_t pair = __builtin_nontemporal_load(base + ((int64_t)row * n2_len + n2) * width + c);
+    data[phys(row, c, lg)] = make_float2(bf16_lo(pair), bf16_hi(pair));
+  }
+  __syncthreads();
+  transform(data, tw, p1, n1, lg, -1.f);
+  float2* out = scratch + (int64_t)strip * cp;
+  for (int e = threadIdx.x; e < (n1 << lg); e += kFreqThreads) {
+    const int k1 = e >> lg, c = e & (cp - 1);
+    out[((int64_t)k1 * n2_len + n2) * width + c] = cmul(data[phys(k1, c, lg)], long_twiddle(n2, k1, n, -1.f));
+  }
+}
+
+// B: one workgroup = one k1 and one strip; rows k1 N2 ... k1 N2 + N2 - 1 of the scratch array, in place.
+__global__ __launch_bounds__(kFreqThreads) void freq_long_b_kernel(float2* __restrict__ scratch, int32_t width, FftPlan p2,
+                                                                   int32_t n, int32_t n1_len, int32_t cutoff) {
+  extern __shared__ float2 lds[];
+  int n2 = p2.n, lg = p2.lg_cp;
+  const int cp = 1 << lg;
+  float2* data = lds;
+  float2* tw = lds + ((n2 + (n2 >> 4) + 1) << lg);
+  const int strips = width >> lg;
+  const int strip = blockIdx.x % strips, k1 = blockIdx.x / strips;
+  build_twiddles(tw, n2);
+  float2* rows = scratch + (int64_t)k1 * n2 * width + (int64_t)strip * cp;
+  for (int e = threadIdx.x; e < (n2 << lg); e += kFreqThreads) {
+    const int row = e >> lg, c = e & (cp - 1);
+    data[phys(row, c, lg)] = rows[(int64_t)row * width + c];
+  }
+  __syncthreads();
+  transform(data, tw, p2, n2, lg, -1.f);
+  // Eq. 3: bin k = k1 + N1 k2 goes when cutoff <= k <= N - cutoff
+  for (int e = threadIdx.x; e < (n2 << lg); e += kFreqThreads) {
+    const int k2 = e >> lg, c = e & (cp - 1);
+    const int k = k1 + n1_len * k2;
+    if (k >= cutoff && k <= n - cutoff) data[phys(k2, c, lg)] = make_float2(0.f, 0.f);
+  }
+  __syncthreads();
+  transform(data, tw, p2, n2, lg, 1.f);
+  for (int e = threadIdx.x; e < (n2 << lg); e += kFreqThreads) {
+    const int j = e >> lg, c = e & (cp - 1);
+    rows[(int64_t)j * width + c] = cmul(data[phys(j, c, lg)], long_twiddle(j, k1, n, 1.f));
+  }
+}
+
+// C: one workgroup = one n2 and one strip; partial[strip * n + token] = sum over the strip of |N x~|^2.
+__global__ __launch_bounds__(kFreqThreads) void freq_long_c_kernel(const float2* __restrict__ scratch, int32_t width,
+                                                                   FftPlan p1, int32_t n, int32_t n2_len,
+                                                                   float* __restrict__ partial) {
+  extern __shared__ float2 lds[];
+  int n1 = p1.n, lg = p1.lg_cp;
+  const int cp = 1 << lg;
+  float2* data = lds;
+  float2* tw = lds + ((n1 + (n1 >> 4) + 1) << lg);
+  const int strips = width >> lg;
+  const int strip = blockIdx.x % strips, n2 = blockIdx.x / strips;
+  build_twiddles(tw, n1);
+  const float2* in = scratch + (int64_t)strip * cp;
+  for (int e = threadIdx.x; e < (n1 << lg); e += kFreqThreads) {
+    const int k1 = e >> lg, c = e & (cp - 1);
+    data[phys(k1, c, lg)] = in[((int64_t)k1 * n2_len + n2) * width + c];
+  }
+  __syncthreads();
+  transform(data, tw, p1, n1, lg, 1.f);
+  // Eq. 5: a token's squares over the strip, summed by one thread in a fixed order
+  for (int row = threadIdx.x; row < n1; row += kFreqThreads) {
+    const float2* line = data + phys(row, 0, lg);
+    float sq = 0.f;
+    for (int q = 0; q < cp; ++q) {
+      const float2 x = line[(q + row) & (cp - 1)];
+      sq = fmaf(x.x, x.x, fmaf(x.y, x.y, sq));
+    }
+    partial[(int64_t)strip * n + (int64_t)row * n2_len + n2] = sq;
+  }
+}
+
 // Eq. 5-6: s_i = (||K~_i|| + ||V~_i||) / 2
 __global__ __launch_bounds__(256) void freq_finish_kernel(const float* __restrict__ partial, int32_t n, int32_t groups,
                                                           int32_t n_batch, float* __restrict__ scores) {
@@ -452,7 +569,7 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float* __restrict__ sc
 }
 
 // ---- host side ------------------------------------------------------------------------------
-static bool make_plan(int32_t n, int32_t row_elems, double alpha, int32_t n_batch, FftPlan* p) {
+static bool factor_radices(int32_t n, FftPlan* p) {
   p->n = n;
   p->n_pass = 0;
   int rest = n;
@@ -465,16 +582,58 @@ static bool make_plan(int32_t n, int32_t row_elems, double alpha, int32_t n_batc
       rest /= r;
     }
   }
-  if (rest != 1) return false;
-  int lg = 0;
-  while ((2 << lg) <= 64 && (int64_t)n * (2 << lg) <= kFreqMaxElems && row_elems % (4 << lg) == 0) ++lg;
-  if (row_elems % (2 << lg) != 0) return false;
-  p->lg_cp = lg;
+  return rest == 1;
+}
+
+static int32_t cutoff_bins(int32_t n, double alpha) {
   const int bins = n / 2 + 1;
   int c = (int)floor(alpha * bins + 1e-9);
   if (c < 0) c = 0;
   if (c > bins) c = bins;
-  p->cutoff = c;
+  return c;
+}
+
+// Long sequences: N = N1 N2 with N1 <= N2 <= kFreqMaxTokens, N1 the largest such divisor.
+struct LongPlan {
+  FftPlan p1, p2;
+  int32_t width;        // complex columns per row = row_elems / 2
+  int32_t cutoff;
+  size_t partial_bytes, scratch_bytes;
+};
+static bool make_long_plan(int32_t n, int32_t row_elems, double alpha, LongPlan* lp) {
+  if (row_elems % 2 != 0 || n >= (1 << 24)) return false;
+  int n1 = 0;
+  for (int d = (int)floor(sqrt((double)n)); d >= 2; --d)
+    if (n % d == 0) {
+      if (n / d <= kFreqMaxTokens) n1 = d;
+      break;                       // the largest divisor below the root; smaller ones have larger cofactors
+    }
+  if (n1 == 0) return false;
+  *lp = LongPlan{};
+  if (!factor_radices(n1, &lp->p1) || !factor_radices(n / n1, &lp->p2)) return false;
+  lp->width = row_elems / 2;
+  for (FftPlan* p : {&lp->p1, &lp->p2}) {
+    int lg = 0;
+    while (((int64_t)p->n << (lg + 1)) <= kFreqLongElems && lp->width % (2 << lg) == 0) ++lg;
+    p->lg_cp = lg;
+  }
+  lp->cutoff = cutoff_bins(n, alpha);
+  const size_t strips_c = (size_t)lp->width >> lp->p1.lg_cp;
+  lp->partial_bytes = strips_c * n * sizeof(float);                            // per tensor
+  lp->scratch_bytes = ((size_t)n * lp->width * sizeof(float2) + 255) & ~(size_t)255;
+  return true;
+}
+static size_t long_lds_bytes(const FftPlan& p) {
+  return ((size_t)((p.n + (p.n >> 4) + 1) << p.lg_cp) + (size_t)(p.n + 1) / 2) * sizeof(float2);
+}
+
+static bool make_plan(int32_t n, int32_t row_elems, double alpha, int32_t n_batch, FftPlan* p) {
+  if (!factor_radices(n, p)) return false;
+  int lg = 0;
+  while ((2 << lg) <= 64 && (int64_t)n * (2 << lg) <= kFreqMaxElems && row_elems % (4 << lg) == 0) ++lg;
+  if (row_elems % (2 << lg) != 0) return false;
+  p->lg_cp = lg;
+  p->cutoff = cutoff_bins(n, alpha);
   p->strips = row_elems / (2 << lg);
   // one strip per workgroup.  The split depends on the shape alone, not on the batch, so that a
   // sequence gets the same bits whatever it is batched with.
@@ -495,9 +654,13 @@ extern "C" {
 
 size_t ct_frequency_workspace_bytes(int32_t n_batch, int32_t n_tokens, int32_t row_elems) {
   FftPlan p;
-  if (n_batch <= 0 || n_tokens <= 0 || n_tokens > kFreqMaxTokens || row_elems <= 0 ||
-      !make_plan(n_tokens, row_elems, 0.5, n_batch, &p))
-    return 0;
+  if (n_batch <= 0 || n_tokens <= 0 || row_elems <= 0) return 0;
+  if (n_tokens > kFreqMaxTokens) {
+    LongPlan lp;
+    if (!make_long_plan(n_tokens, row_elems, 0.5, &lp)) return 0;
+    return (((size_t)n_batch * 2 * lp.partial_bytes + 255) & ~(size_t)255) + lp.scratch_bytes;
+  }
+  if (!make_plan(n_tokens, row_elems, 0.5, n_batch, &p)) return 0;
   return (size_t)n_batch * 2 * p.groups * n_tokens * sizeof(float);
 }
 
@@ -511,16 +674,54 @@ ct_status ct_frequency_scores(const void* k, const void* v, int32_t n_batch, int
   if (row_elems % 2 != 0) return fail(CT_ERR_SHAPE, "row_elems %d must be even", row_elems);
   if (n_batch > 1 && batch_stride < (int64_t)n_tokens * row_elems)
     return fail(CT_ERR_SHAPE, "batch_stride %lld is smaller than one sequence", (long long)batch_stride);
-  if (n_tokens > kFreqMaxTokens)
-    return fail(CT_ERR_UNSUPPORTED, "n_tokens %d: sequences longer than %d tokens do not fit the in-LDS transform",
-                n_tokens, kFreqMaxTokens);
+  hipStream_t s = (hipStream_t)stream;
+  if (n_tokens > kFreqMaxTokens) {
+    LongPlan lp;
+    if (!make_long_plan(n_tokens, row_elems, alpha, &lp))
+      return fail(CT_ERR_UNSUPPORTED,
+                  "n_tokens %d: needs a divisor pair N1 N2 with both at most %d and no prime factor above 5, below 2^24",
+                  n_tokens, kFreqMaxTokens);
+    const size_t partial_all = ((size_t)n_batch * 2 * lp.partial_bytes + 255) & ~(size_t)255;
+    const size_t need = partial_all + lp.scratch_bytes;
+    if (workspace == nullptr || workspace_bytes < need)
+      return fail(CT_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    if (((uintptr_t)workspace & 255) != 0) return fail(CT_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    for (const void* fn : {(const void*)freq_long_a_kernel, (const void*)freq_long_b_kernel, (const void*)freq_long_c_kernel}) {
+      hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (ea != hipSuccess) return hip_fail(ea, "hipFuncSetAttribute(long-sequence frequency kernels)");
+    }
+    float* partial = (float*)workspace;
+    float2* scratch = (float2*)((char*)workspace + partial_all);
+    const int n1 = lp.p1.n, n2 = lp.p2.n;
+    const unsigned grid_ac = (unsigned)((size_t)n2 * (lp.width >> lp.p1.lg_cp));
+    const unsigned grid_b = (unsigned)((size_t)n1 * (lp.width >> lp.p2.lg_cp));
+    const int groups = lp.width >> lp.p1.lg_cp;
+    // one tensor at a time through the one scratch array (the launches of a stream run in order)
+    for (int t = 0; t < n_batch * 2; ++t) {
+      const uint16_t* src = (const uint16_t*)((t & 1) ? v : k) + (int64_t)(t >> 1) * batch_stride;
+      launch_kernel(KC_FREQ, freq_long_a_kernel, dim3(grid_ac), dim3(kFreqThreads), (unsigned)long_lds_bytes(lp.p1), s, src,
+                    lp.width, lp.p1, n_tokens, n2, scratch);
+      launch_kernel(KC_FREQ, freq_long_b_kernel, dim3(grid_b), dim3(kFreqThreads), (unsigned)long_lds_bytes(lp.p2), s, scratch,
+                    lp.width, lp.p2, n_tokens, n1, lp.cutoff);
+      launch_kernel(KC_FREQ, freq_long_c_kernel, dim3(grid_ac), dim3(kFreqThreads), (unsigned)long_lds_bytes(lp.p1), s,
+                    (const float2*)scratch, lp.width, lp.p1, n_tokens, n2,
+                    partial + (size_t)t * (lp.partial_bytes / sizeof(float)));
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "long-sequence frequency score launch");
+    const int64_t total = (int64_t)n_batch * n_tokens;
+    launch_kernel(KC_FREQ, freq_finish_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                  (const float*)partial, n_tokens, groups, n_batch, scores);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "frequency score finish launch");
+    return CT_OK;
+  }
   FftPlan p;
   if (!make_plan(n_tokens, row_elems, alpha, n_batch, &p))
     return fail(CT_ERR_UNSUPPORTED, "n_tokens %d has a prime factor above 5", n_tokens);
   const size_t need = (size_t)n_batch * 2 * p.groups * n_tokens * sizeof(float);
   if (workspace == nullptr || workspace_bytes < need)
     return fail(CT_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
-  hipStream_t s = (hipStream_t)stream;
   // power-of-two lengths from 256 on whose strips hold the full kFreqMaxElems values take the kernel
   // with the plan compiled in; everything else the one that reads the plan at run time
   using Kernel = void (*)(const uint16_t*, const uint16_t*, int64_t, int32_t, int32_t, FftPlan, float*);

@@ -316,7 +316,11 @@ def test_frequency_selection_argument_checks():
     def scores(n_batch=1, stride=2048 * 1024, n=2048, row=1024, alpha=0.5, k=one, v=one, out=one, ws=one, ws_bytes=1 << 30):
         return lib.ct_frequency_scores(k, v, n_batch, stride, n, row, alpha, out, ws, ws_bytes, None)
     assert scores(n=7 * 128) == B.CT_ERR_UNSUPPORTED          # prime factor 7
-    assert scores(n=8192, stride=8192 * 1024) == B.CT_ERR_UNSUPPORTED
+    # beyond 4096 tokens the transform is split in two factors of at most 4096 each
+    assert scores(n=2 * 4099, stride=2 * 4099 * 1024) == B.CT_ERR_UNSUPPORTED       # 4099 is prime
+    assert scores(n=1 << 24, stride=(1 << 24) * 1024) == B.CT_ERR_UNSUPPORTED
+    assert scores(n=8192, stride=8192 * 1024, ws_bytes=1 << 20) == B.CT_ERR_WORKSPACE
+    assert scores(n=8192, stride=8192 * 1024, ws=ctypes.c_void_p(264)) == B.CT_ERR_WORKSPACE   # alignment
     assert scores(row=1023) == B.CT_ERR_SHAPE
     assert scores(alpha=1.5) == B.CT_ERR_RATIO and scores(alpha=-0.1) == B.CT_ERR_RATIO
     assert scores(k=None) == B.CT_ERR_NULL and scores(out=None) == B.CT_ERR_NULL
@@ -324,7 +328,9 @@ def test_frequency_selection_argument_checks():
     assert scores(ws_bytes=16) == B.CT_ERR_WORKSPACE and scores(ws=None) == B.CT_ERR_WORKSPACE
     assert scores(n_batch=0) == B.CT_OK and scores(n=0) == B.CT_OK
     assert B.ct_frequency_workspace_bytes(1, 2048, 1024) == 2 * 64 * 2048 * 4
-    assert B.ct_frequency_workspace_bytes(1, 8192, 1024) == 0 and B.ct_frequency_workspace_bytes(1, 7, 8) == 0
+    # 8192 = 64 x 128: four strips of 128 complex columns per tensor, and one complex fp32 copy of a tensor
+    assert B.ct_frequency_workspace_bytes(1, 8192, 1024) == 2 * 4 * 8192 * 4 + 8192 * 512 * 8
+    assert B.ct_frequency_workspace_bytes(1, 2 * 4099, 1024) == 0 and B.ct_frequency_workspace_bytes(1, 7, 8) == 0
     assert lib.ct_topk_indices(one, 1, 10, 11, one, None) == B.CT_ERR_SHAPE
     assert lib.ct_topk_indices(None, 1, 10, 3, one, None) == B.CT_ERR_NULL
     assert lib.ct_topk_indices(one, 1, 10, 0, one, None) == B.CT_OK

@@ -55,6 +55,15 @@ def _oracle_scores(kb, vb, alpha):
     (512, 256, 1, 0.002),     # c = 0 as well (floor(0.002 * 257) = 0)
     (512, 256, 1, 0.004),     # c = 1: the mean over the tokens only
     (2, 8, 1, 0.5), (1, 8, 1, 1.0), (1, 8, 1, 0.5), (3, 2, 1, 1.0),
+    # beyond 4096 tokens: N = N1 N2 through HBM
+    (8192, 1024, 1, 0.5),     # 64 x 128, full-width rows
+    (32768, 64, 2, 0.3),      # 128 x 256, a whole config-3 context as one sequence
+    (6000, 32, 2, 0.3),       # 75 x 80: radices 5, 5, 3 and 16, 5
+    (5000, 6, 1, 0.5),        # 50 x 100, one complex column per strip (odd width)
+    (12288, 256, 1, 1.0),     # 96 x 128, everything kept: the plain row norm
+    (8192, 64, 1, 0.0),       # nothing kept
+    (8192, 64, 1, 0.0003),    # c = 1: the mean over the tokens only
+    (131072, 16, 1, 0.1),     # 256 x 512, config 4's context length
 ])
 def test_scores_match_oracle(n, row, n_batch, alpha):
     say(f"frequency scores n={n} row={row} batch={n_batch} alpha={alpha}")
@@ -79,6 +88,11 @@ def test_scores_are_reproducible_and_batch_independent():
     assert torch.equal(a, b)
     one = _gpu_scores(kb[2:3], vb[2:3], 0.5)
     assert torch.equal(one[0], a[2])
+    say("the same for a sequence beyond 4096 tokens")
+    kb, vb = W.make_spectral_kv(78, 8192, 256, 3)
+    a = _gpu_scores(kb, vb, 0.5)
+    assert torch.equal(a, _gpu_scores(kb, vb, 0.5))
+    assert torch.equal(_gpu_scores(kb[1:2], vb[1:2], 0.5)[0], a[1])
 
 
 @pytest.mark.parametrize("n,n_batch", [(1, 1), (7, 2), (1024, 3), (1025, 1), (4096, 2), (100000, 1)])
@@ -112,7 +126,7 @@ def test_topk_is_bit_exact(n, n_batch):
 
 
 @pytest.mark.parametrize("n,row,n_batch,ratio", [(2048, 1024, 2, 0.15), (256, 128, 1, 0.05), (3072, 1024, 1, 0.3),
-                                                 (64, 16, 1, 0.001), (64, 16, 1, 1.0)])
+                                                 (64, 16, 1, 0.001), (64, 16, 1, 1.0), (16384, 128, 1, 0.15)])
 def test_selection_end_to_end(n, row, n_batch, ratio):
     say(f"select_frequency n={n} row={row} batch={n_batch} ratio={ratio}")
     alpha = 0.5
