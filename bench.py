@@ -34,7 +34,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # summary under profiles/).
 MEASURED_ATTENTION_TRAFFIC = {
     # workload: (fetch MiB scaled, write MiB, sha256 prefix of ct_attention.hip, summary file)
-    "cfg3-llama8b-32k-r15": (581.2, 40.8, "8f3136a6a6419702", "profiles/partial_prefill_layer_cfg3_r15.md"),
+    "cfg3-llama8b-32k-r15": (576.1, 40.8, "68d23583b46a9d35", "profiles/partial_prefill_layer_cfg3_r15.md"),
 }
 
 
