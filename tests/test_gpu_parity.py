@@ -412,3 +412,53 @@ def test_layer_config2():
     wl = W.make_workload(W.spec(2))
     out, kb, vb = _run_layer(wl)
     _check_layer(wl, out, kb, vb)
+
+
+def test_layer_call_can_be_captured_in_a_hip_graph():
+    """The layer call with a device-resident pool only enqueues kernels on the caller's stream (no
+    allocation, no synchronisation, no memset), so a caller may capture it.  The graph is replayed
+    three times with eager work and synchronisation between the replays and with the outputs wiped
+    before each; every replay must give the bits of the eager call, which the oracle bounds."""
+    wl = W.make_workload(W.spec(2))
+    sp, sh = wl.spec, wl.spec.shape
+    cfg = B.cfg_from_shape(sh)
+    n_ctx, n_sel, n_chunks = sp.n_ctx, sp.n_sel, len(wl.chunk_rows) - 1
+    hidden, wqkv, sel = dev_bf16(wl.hidden), dev_bf16(wl.wqkv), dev_i32(wl.sel_idx)
+    rows = None if wl.hidden_rows is None else dev_i32(wl.hidden_rows)
+    k_pool, v_pool = dev_bf16(wl.k_cache), dev_bf16(wl.v_cache)
+    k_buf = torch.zeros((n_ctx, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_buf = torch.zeros_like(k_buf)
+    chunks = B.make_chunks([dict(k=k_pool[int(wl.chunk_rows[c]):int(wl.chunk_rows[c + 1])],
+                                 v=v_pool[int(wl.chunk_rows[c]):int(wl.chunk_rows[c + 1])],
+                                 n_tokens=int(wl.chunk_rows[c + 1] - wl.chunk_rows[c]), old_pos_start=int(wl.chunk_old_start[c]),
+                                 new_pos_start=int(wl.chunk_new_start[c]), location=0) for c in range(n_chunks)])
+    ws_bytes = B.ct_workspace_bytes(cfg, n_ctx, n_sel)
+    ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    out = torch.zeros((n_sel, sh.n_q_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")
+    side = torch.cuda.Stream()
+
+    def step(stream):
+        B.ct_partial_prefill_layer(cfg, chunks, n_chunks, hidden, rows, sel, n_sel, sp.ratio_pct / 100.0, wqkv, None,
+                                   k_buf, v_buf, out, ws, ws_bytes, stream, stream)
+
+    say("layer cfg2, eager call on a side stream")
+    step(side)
+    torch.cuda.synchronize()
+    want_out, want_k, want_v = out.clone(), k_buf.clone(), v_buf.clone()
+    _check_layer(wl, want_out, want_k, want_v)
+    say("layer cfg2, capture")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(torch.cuda.current_stream())
+    for replay in range(3):
+        out.fill_(float("nan")); k_buf.fill_(float("nan")); v_buf.fill_(float("nan")); ws.fill_(0xff)
+        torch.cuda.synchronize()
+        say(f"layer cfg2, graph replay {replay}")
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want_out.view(torch.int16)), f"replay {replay}: attention output differs"
+        assert torch.equal(k_buf.view(torch.int16), want_k.view(torch.int16)), f"replay {replay}: fused K differs"
+        assert torch.equal(v_buf.view(torch.int16), want_v.view(torch.int16)), f"replay {replay}: fused V differs"
+        step(side)                                     # eager work of the same kind between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want_out.view(torch.int16))
