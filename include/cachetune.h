@@ -66,7 +66,8 @@ typedef struct {
  * memory (location 1).  Location 2 is a pool that dropped the recompute set when the chunk was
  * offloaded (Sec. 4.2, index-aware offloading): pinned host memory holding, in order, only the
  * chunk's rows that are NOT in sel_idx - n_tokens minus the number of selected rows of the
- * chunk; n_tokens still counts all tokens of the chunk.  In the new context token t of the chunk sits at position
+ * chunk; n_tokens still counts all tokens of the chunk (k and v must be non-NULL even when no row
+ * of the chunk is kept: nothing is read then).  In the new context token t of the chunk sits at position
  * new_pos_start + t.  raw_keys = 0: the keys were cached after RoPE at positions
  * old_pos_start + t and are rotated by new_pos_start - old_pos_start.  raw_keys = 1: the
  * keys were cached before RoPE (the paper's own scheme, Eq. 8) and token t is rotated by
