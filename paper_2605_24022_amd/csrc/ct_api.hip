@@ -116,7 +116,10 @@ AttnPlan plan_attention(const ct_layer_cfg* cfg, int n_ctx, int n_sel) {
   // measured on MI355X, an unsplit launch wins as soon as there are about 1.5 pairs per
   // compute unit (each split costs an fp32 partial (O, m, l) round trip and a merge kernel).
   const long pairs = (long)p.n_tiles * cfg->n_kv_heads;
-  const long target = 384;                              // 1.5 x 256 compute units
+  static const long target = []() {                     // tuning knob: split below this many (tile, head) pairs
+    const char* v = getenv("CT_ATTN_SPLIT_TARGET");
+    return v != nullptr && atol(v) > 0 ? atol(v) : 384L;  // 1.5 x 256 compute units
+  }();
   if (pairs > 0 && pairs < target && n_ctx > 2048) {
     int want = (int)((target + pairs - 1) / pairs);
     int keys = (n_ctx + want - 1) / want;
